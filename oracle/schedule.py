@@ -1,0 +1,261 @@
+"""CPU oracle, part 3: from weighted trees to a chunked step list (paper
+sections 3.3, 4.1, 4.2.1, 4.2.2).
+
+TEST INFRASTRUCTURE ONLY (see oracle/graph.py).  Shares no code with the HIP
+library's scheduler; the library's step list is checked with the validators at
+the bottom of this file.
+
+What the paper fixes:
+  * the payload is split among the trees in proportion to their weights
+    (section 4.1);
+  * each tree's share is cut into chunks, the unit of transfer and of
+    synchronisation: a node forwards a chunk only once it holds all of it
+    (section 4.2.1);
+  * Broadcast sends every chunk along every tree arc, root outwards;
+    AllReduce first reduces towards the root over the reversed arcs, then
+    broadcasts the result back over the same tree (section 3.3): 2(N-1)
+    transfers per chunk on a tree of N vertices.
+
+Readings where the paper is silent:
+  * split boundaries: b_t = floor(n * (w_1+..+w_t) / W) rounded down to a
+    multiple of ``align`` elements (4 = one 128-bit access) for 0 < t < T;
+    b_0 = 0, b_T = n;
+  * chunks have exactly C elements except a short last chunk per tree;
+  * a node with several children folds them in ascending vertex id, one at a
+    time, in place: parent <- parent + child.  This fixes the floating-point
+    association order.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from fractions import Fraction
+from typing import Dict, List, Sequence, Tuple
+
+from .graph import children_of
+
+REDUCE = 0  # dst[off:off+len] <- dst[off:off+len] + src[off:off+len]
+COPY = 1    # dst[off:off+len] <- src[off:off+len]
+
+BROADCAST = 0
+ALLREDUCE = 1
+
+
+@dataclass(frozen=True)
+class Step:
+    kind: int          # REDUCE or COPY
+    tree: int
+    chunk: int         # chunk index inside the tree's share
+    src: int           # rank read
+    dst: int           # rank written (and, for REDUCE, also read)
+    off: int           # first element
+    len: int           # number of elements
+    deps: Tuple[int, ...]  # indices of earlier steps that must complete first
+
+
+def split_by_weight(n: int, weights: Sequence[float], align: int = 4) -> List[int]:
+    """Boundaries b_0..b_T of the per-tree shares of [0, n).  Exact rational
+    arithmetic on the given weights."""
+    fr = [Fraction(w) for w in weights]
+    total = sum(fr)
+    bounds = [0]
+    acc = Fraction(0)
+    for w in fr[:-1]:
+        acc += w
+        b = int(math.floor(n * acc / total))
+        b -= b % align
+        bounds.append(max(b, bounds[-1]))
+    bounds.append(n)
+    return bounds
+
+
+def chunk_ranges(lo: int, hi: int, chunk: int) -> List[Tuple[int, int]]:
+    """(offset, length) of the chunks tiling [lo, hi)."""
+    if chunk <= 0:
+        raise ValueError("chunk must be positive")
+    return [(o, min(chunk, hi - o)) for o in range(lo, hi, chunk)]
+
+
+def reduce_order(root: int, parent: Sequence[int]) -> List[int]:
+    """Non-root vertices, every vertex after all vertices of its subtree
+    (post-order, children ascending): the order of the child->parent
+    transfers of the reduce phase."""
+    ch = children_of(parent)
+    out: List[int] = []
+
+    def visit(v: int) -> None:
+        for c in ch[v]:
+            visit(c)
+        if v != root:
+            out.append(v)
+
+    visit(root)
+    return out
+
+
+def broadcast_order(root: int, parent: Sequence[int]) -> List[int]:
+    """Non-root vertices in breadth-first order from the root (children
+    ascending): the order of the parent->child transfers."""
+    ch = children_of(parent)
+    out: List[int] = []
+    frontier = [root]
+    while frontier:
+        nxt: List[int] = []
+        for v in frontier:
+            for c in ch[v]:
+                out.append(c)
+                nxt.append(c)
+        frontier = nxt
+    return out
+
+
+def make_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
+               weights: Sequence[float], op: int, n: int, chunk: int) -> List[Step]:
+    """The whole step list: tree by tree, chunk by chunk, reduce phase then
+    broadcast phase.  Dependencies name the steps that produce a step's inputs:
+
+    REDUCE v->p waits for the REDUCE out of v's last child (v then holds the
+    sum of its subtree, because siblings are chained) and for the REDUCE of
+    p's previous child (in-place accumulation in ascending child order).
+    COPY p->v waits for the COPY into p, or, when p is the root, for the last
+    REDUCE into the root (none for a plain Broadcast)."""
+    bounds = split_by_weight(n, weights)
+    steps: List[Step] = []
+    for t, (root, parent) in enumerate(zip(roots, trees)):
+        ch = children_of(parent)
+        for c, (off, ln) in enumerate(chunk_ranges(bounds[t], bounds[t + 1], chunk)):
+            red: Dict[int, int] = {}   # vertex -> index of its REDUCE-out step
+            cp: Dict[int, int] = {}    # vertex -> index of the COPY into it
+            if op == ALLREDUCE:
+                for v in reduce_order(root, parent):
+                    p = parent[v]
+                    deps = []
+                    if ch[v]:
+                        deps.append(red[ch[v][-1]])
+                    i = ch[p].index(v)
+                    if i > 0:
+                        deps.append(red[ch[p][i - 1]])
+                    red[v] = len(steps)
+                    steps.append(Step(REDUCE, t, c, v, p, off, ln, tuple(deps)))
+            for v in broadcast_order(root, parent):
+                p = parent[v]
+                if p != root:
+                    deps = (cp[p],)
+                elif op == ALLREDUCE:
+                    deps = (red[ch[root][-1]],)
+                else:
+                    deps = ()
+                cp[v] = len(steps)
+                steps.append(Step(COPY, t, c, p, v, off, ln, deps))
+    return steps
+
+
+# --------------------------------------------------------------------------
+# validators for ANY scheduler's step list
+# --------------------------------------------------------------------------
+def check_split(bounds: Sequence[int], n: int, weights: Sequence[float], align: int = 4) -> None:
+    """Shares are contiguous, disjoint, cover [0, n) and are within one
+    alignment unit of n * w_t / W."""
+    T = len(weights)
+    assert len(bounds) == T + 1 and bounds[0] == 0 and bounds[-1] == n
+    W = sum(Fraction(w) for w in weights)
+    for t in range(T):
+        assert bounds[t] <= bounds[t + 1]
+        if 0 < t:
+            assert bounds[t] % align == 0 or bounds[t] == n
+        ideal = n * Fraction(weights[t]) / W
+        assert abs((bounds[t + 1] - bounds[t]) - ideal) < align + 1, (t, bounds, float(ideal))
+
+
+def check_steps(steps: Sequence[Step], k: int, roots: Sequence[int],
+                trees: Sequence[Sequence[int]], weights: Sequence[float], op: int,
+                n: int, chunk: int) -> None:
+    """Structural checks on a step list produced by anyone:
+      * dependencies point backwards (hence the graph is acyclic);
+      * per tree the chunks tile the tree's share exactly once;
+      * per (tree, chunk): exactly one COPY per tree arc parent->child and, for
+        AllReduce, exactly one REDUCE per reversed arc child->parent;
+      * replaying the list in order with symbolic contents gives, at every
+        rank, the tree-order sum over all ranks (AllReduce) or the root's
+        value (Broadcast), and every step reads only values its listed
+        dependencies (transitively) made final."""
+    bounds = split_by_weight(n, weights)
+    for i, s in enumerate(steps):
+        assert all(0 <= d < i for d in s.deps), f"step {i}: dependency not earlier"
+        assert 0 <= s.src < k and 0 <= s.dst < k and s.src != s.dst
+    by_tc: Dict[Tuple[int, int], List[int]] = {}
+    for i, s in enumerate(steps):
+        by_tc.setdefault((s.tree, s.chunk), []).append(i)
+    for t, (root, parent) in enumerate(zip(roots, trees)):
+        want = chunk_ranges(bounds[t], bounds[t + 1], chunk)
+        got = sorted({(steps[ix[0]].off, steps[ix[0]].len) for (tt, _), ix in by_tc.items() if tt == t})
+        assert got == want, f"tree {t}: chunks {got[:3]}.. do not tile {want[:3]}.."
+        arcs = sorted((parent[v], v) for v in range(k) if v != root)
+        for (tt, c), ix in by_tc.items():
+            if tt != t:
+                continue
+            off, ln = steps[ix[0]].off, steps[ix[0]].len
+            assert all(steps[i].off == off and steps[i].len == ln for i in ix)
+            copies = sorted((steps[i].src, steps[i].dst) for i in ix if steps[i].kind == COPY)
+            reduces = sorted((steps[i].dst, steps[i].src) for i in ix if steps[i].kind == REDUCE)
+            assert copies == arcs, f"tree {t} chunk {c}: COPY steps do not match the tree arcs"
+            assert reduces == (arcs if op == ALLREDUCE else []), \
+                f"tree {t} chunk {c}: REDUCE steps do not match the reversed tree arcs"
+            _symbolic_replay(steps, ix, k, root, parent, op)
+
+
+def _tree_order_expr(v: int, ch: List[List[int]]):
+    """Nested tuple standing for ((x_v + S(c1)) + S(c2)) + ..."""
+    e = ("x", v)
+    for c in ch[v]:
+        e = ("+", e, _tree_order_expr(c, ch))
+    return e
+
+
+def _symbolic_replay(steps, idx, k, root, parent, op) -> None:
+    """Run one (tree, chunk)'s steps on symbolic values.  Each rank's cell holds
+    (expression, index of the step that wrote it or -1).  A step may only read a
+    cell whose writer is among its transitive dependencies, and may only
+    overwrite a cell whose earlier readers are among them too."""
+    ch = children_of(parent)
+    val = [(("x", v), -1) for v in range(k)]
+    readers: List[List[int]] = [[] for _ in range(k)]
+    closure: Dict[int, set] = {}
+    for i in idx:
+        s = steps[i]
+        cl = set()
+        for d in s.deps:
+            cl.add(d)
+            cl |= closure.get(d, set())
+        closure[i] = cl
+        reads = [s.src] + ([s.dst] if s.kind == REDUCE else [])
+        for r in reads:
+            w = val[r][1]
+            assert w == -1 or w in cl, f"step {i} reads rank {r} before step {w} is ordered"
+        for rd in readers[s.dst]:
+            assert rd in cl, f"step {i} overwrites rank {s.dst} while step {rd} may still read it"
+        w = val[s.dst][1]
+        assert w == -1 or w in cl, f"step {i} overwrites rank {s.dst} unordered with its writer {w}"
+        if s.kind == REDUCE:
+            val[s.dst] = (("+", val[s.dst][0], val[s.src][0]), i)
+        else:
+            val[s.dst] = (val[s.src][0], i)
+        readers[s.dst] = []
+        readers[s.src].append(i)
+    want = _tree_order_expr(root, ch) if op == ALLREDUCE else ("x", root)
+    for v in range(k):
+        assert val[v][0] == want, f"rank {v} ends with {val[v][0]}, expected {want}"
+
+
+def pipeline_makespan(steps: Sequence[Step]) -> int:
+    """Length, in unit chunk-transfer times, of the schedule when every step
+    takes one time unit, starts once its dependencies are done, and a directed
+    link (src, dst) carries one step at a time in list order.  Used for the
+    chunking claim of section 4.2.1 (h hops, c equal chunks: h + c - 1)."""
+    finish: List[int] = []
+    link_free: Dict[Tuple[int, int], int] = {}
+    for s in steps:
+        start = max([finish[d] for d in s.deps] + [link_free.get((s.src, s.dst), 0)])
+        finish.append(start + 1)
+        link_free[(s.src, s.dst)] = start + 1
+    return max(finish) if finish else 0

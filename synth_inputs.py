@@ -1,0 +1,189 @@
+"""Seeded synthetic inputs: interconnect topologies and rank payloads.
+
+This module is shared by the CPU oracle's tests, the GPU parity tests and the
+benchmark.  It holds no arithmetic of the method itself (no packing, no
+splitting, no reduction): it only describes graphs and draws random payloads.
+
+Topologies are returned as ``Topology`` records: ``k`` vertices and arrays
+``src``, ``dst``, ``cap`` of directed arcs (a bidirectional link is two arcs),
+the graph model of the paper's section 3.1.
+
+Payloads come from a counter-style recipe: block ``b`` of rank ``r`` under seed
+``s`` is drawn from ``numpy.random.default_rng([s, r, b])`` in blocks of
+``BLOCK`` elements, so any slice can be regenerated without holding the rest.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Iterable, List, Sequence, Tuple
+
+import numpy as np
+
+BLOCK = 1 << 20  # elements per independently seeded block
+
+
+# --------------------------------------------------------------------------
+# topologies
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Topology:
+    k: int
+    src: np.ndarray  # int32 [m]
+    dst: np.ndarray  # int32 [m]
+    cap: np.ndarray  # float64 [m]
+    name: str = ""
+
+    @property
+    def m(self) -> int:
+        return int(self.src.shape[0])
+
+    def arcs(self) -> List[Tuple[int, int, float]]:
+        return [(int(u), int(v), float(c)) for u, v, c in zip(self.src, self.dst, self.cap)]
+
+
+def _from_links(k: int, links: Iterable[Tuple[int, int, float]], name: str) -> Topology:
+    """Each undirected link (a, b, c) becomes arcs a->b and b->a of capacity c."""
+    src, dst, cap = [], [], []
+    for a, b, c in links:
+        src += [a, b]
+        dst += [b, a]
+        cap += [c, c]
+    return Topology(k, np.asarray(src, np.int32), np.asarray(dst, np.int32),
+                    np.asarray(cap, np.float64), name)
+
+
+def complete_graph(k: int, cap: float = 1.0) -> Topology:
+    """Fully connected k-vertex graph (also the model of a non-blocking switch)."""
+    links = [(a, b, cap) for a in range(k) for b in range(a + 1, k)]
+    return _from_links(k, links, f"K{k}")
+
+
+def chain(k: int, cap: float = 1.0) -> Topology:
+    """0 - 1 - ... - (k-1), the depth-test topology of the paper's section 2.2."""
+    return _from_links(k, [(i, i + 1, cap) for i in range(k - 1)], f"chain{k}")
+
+
+def star(k: int, center: int = 0, cap: float = 1.0) -> Topology:
+    """One centre linked to every other vertex (fan-in / fan-out test)."""
+    return _from_links(k, [(center, i, cap) for i in range(k) if i != center], f"star{k}")
+
+
+def ring(k: int, cap: float = 1.0) -> Topology:
+    return _from_links(k, [(i, (i + 1) % k, cap) for i in range(k)], f"ring{k}")
+
+
+def cube_mesh_links(doubled: bool) -> List[Tuple[int, int, float]]:
+    """Hybrid cube-mesh on 8 vertices: {0..3} and {4..7} all-to-all, i <-> i+4.
+
+    ``doubled`` gives capacity 2 to links 0-1, 2-3, 4-5, 6-7 and i <-> i+4 (six
+    link-units into every vertex, as on the second-generation server the paper
+    describes in its figure of the hybrid mesh-cube topology); otherwise every
+    link has capacity 1.
+    """
+    links = []
+    for base in (0, 4):
+        for a in range(base, base + 4):
+            for b in range(a + 1, base + 4):
+                two = doubled and (a, b) in ((0, 1), (2, 3), (4, 5), (6, 7))
+                links.append((a, b, 2.0 if two else 1.0))
+    for i in range(4):
+        links.append((i, i + 4, 2.0 if doubled else 1.0))
+    return links
+
+
+def hybrid_cube_mesh(doubled: bool = False) -> Topology:
+    return _from_links(8, cube_mesh_links(doubled),
+                       "cube_mesh_doubled" if doubled else "cube_mesh")
+
+
+def induced(top: Topology, ranks: Sequence[int]) -> Topology:
+    """Sub-topology on ``ranks`` (a fragmented allocation); vertices renumbered
+    0..len(ranks)-1 in the order given."""
+    pos = {int(r): i for i, r in enumerate(ranks)}
+    keep = [i for i in range(top.m) if int(top.src[i]) in pos and int(top.dst[i]) in pos]
+    src = np.asarray([pos[int(top.src[i])] for i in keep], np.int32)
+    dst = np.asarray([pos[int(top.dst[i])] for i in keep], np.int32)
+    cap = np.asarray([top.cap[i] for i in keep], np.float64)
+    return Topology(len(ranks), src, dst, cap,
+                    f"{top.name}[{','.join(str(r) for r in ranks)}]")
+
+
+def random_digraph(k: int, p: float, seed: int, int_caps: bool = True,
+                   max_cap: int = 3) -> Topology:
+    """Random directed graph guaranteed connected from vertex 0: a random
+    out-tree from 0 plus each other arc with probability p."""
+    rng = np.random.default_rng([seed, k])
+    arcs = {}
+    order = list(rng.permutation(np.arange(1, k)))
+    placed = [0]
+    for v in order:
+        u = placed[int(rng.integers(len(placed)))]
+        arcs[(u, int(v))] = None
+        placed.append(int(v))
+    for u in range(k):
+        for v in range(k):
+            if u != v and rng.random() < p:
+                arcs[(u, v)] = None
+    src, dst, cap = [], [], []
+    for (u, v) in sorted(arcs):
+        src.append(u)
+        dst.append(v)
+        cap.append(float(rng.integers(1, max_cap + 1)) if int_caps
+                   else float(rng.uniform(0.25, max_cap)))
+    return Topology(k, np.asarray(src, np.int32), np.asarray(dst, np.int32),
+                    np.asarray(cap, np.float64), f"rand{k}_{seed}")
+
+
+# --------------------------------------------------------------------------
+# payloads
+# --------------------------------------------------------------------------
+def payload_block(seed: int, rank: int, block: int, dist: str, dtype: str,
+                  scale: float = 1.0, count: int = BLOCK) -> np.ndarray:
+    """One seeded block of ``count`` (<= BLOCK) elements.
+
+    dist: "uniform" (U[-scale, scale]), "normal" (N(0, sigma=scale)),
+          "int" (full-range int32, exercises wrap-around).
+    """
+    rng = np.random.default_rng([seed, rank, block])
+    if dtype == "int32":
+        if dist != "int":
+            raise ValueError("int32 payloads use dist='int'")
+        return rng.integers(-(1 << 31), 1 << 31, size=count, dtype=np.int64).astype(np.int32)
+    if dtype != "fp32":
+        raise ValueError(dtype)
+    if dist == "uniform":
+        return ((rng.random(count, dtype=np.float32) * 2.0 - 1.0) * np.float32(scale)).astype(np.float32)
+    if dist == "normal":
+        return (rng.standard_normal(count, dtype=np.float32) * np.float32(scale)).astype(np.float32)
+    raise ValueError(dist)
+
+
+def payload(seed: int, rank: int, n: int, dist: str, dtype: str, scale: float = 1.0,
+            start: int = 0) -> np.ndarray:
+    """Elements [start, start+n) of rank ``rank``'s payload."""
+    out = np.empty(n, np.int32 if dtype == "int32" else np.float32)
+    pos = start
+    end = start + n
+    while pos < end:
+        b = pos // BLOCK
+        lo = pos - b * BLOCK
+        take = min(end - pos, BLOCK - lo)
+        blk = payload_block(seed, rank, b, dist, dtype, scale)
+        out[pos - start:pos - start + take] = blk[lo:lo + take]
+        pos += take
+    return out
+
+
+def bucket_sizes(total_elems: int = 138_000_000, n_buckets: int = 16, seed: int = 0,
+                 lo_bytes: int = 64 << 10, hi_bytes: int = 400 << 20) -> List[int]:
+    """Per-layer gradient buckets: byte sizes log-uniform in [lo, hi], rescaled to
+    sum to total, clamped to the range, rounded to 4 elements, remainder to the
+    largest bucket.  Returns element counts (fp32/int32)."""
+    rng = np.random.default_rng([seed, 4040])
+    b = np.exp(rng.uniform(np.log(lo_bytes), np.log(hi_bytes), n_buckets))
+    b = b * (total_elems * 4.0 / b.sum())
+    b = np.clip(b, lo_bytes, hi_bytes)
+    e = (np.floor(b / 16.0).astype(np.int64)) * 4
+    e[int(np.argmax(e))] += total_elems - int(e.sum())
+    assert int(e.sum()) == total_elems and (e > 0).all()
+    return [int(x) for x in e]
