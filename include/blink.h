@@ -1,0 +1,179 @@
+/*
+ * blink.h - C ABI of the packed-spanning-tree collectives for one MI355X.
+ *
+ * The k "ranks" of a collective are k separate device (HBM) buffers on the
+ * current HIP device.  A collective is prepared in two host-side steps and then
+ * executed by one persistent gfx950 kernel:
+ *
+ *   blink_pack_trees     topology graph -> weighted spanning trees
+ *                        (paper sections 3.1, 3.2, 3.2.1, 3.5)
+ *   blink_make_schedule  trees + payload size + chunk size -> step list
+ *                        (paper sections 3.3, 4.1, 4.2.1, 4.2.2)
+ *   blink_broadcast /    run the step list on k device buffers, asynchronously
+ *   blink_allreduce      on a HIP stream (paper sections 3.3, 4.1)
+ *
+ * Conventions
+ *   - Every function that can fail returns blink_status_t; results come back
+ *     through pointer arguments.  No exception crosses this boundary.
+ *   - "host" / "device" in a parameter comment says where the pointed-to memory
+ *     must live.
+ *   - Handles (blink_trees_t, blink_schedule_t) are owned by the library and
+ *     released with the matching *_free.  The caller owns every buffer it
+ *     passes in; the library never frees or reallocates caller memory.
+ *   - A schedule keeps device-side progress counters: it may be used by many
+ *     calls one after another on ONE stream at a time.  Two calls that overlap
+ *     in time on the same schedule race.
+ *   - At most BLINK_MAX_RANKS ranks.
+ */
+#ifndef BLINK_H
+#define BLINK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BLINK_MAX_RANKS 16
+/* root argument of blink_pack_trees for switch-like (fully connected)
+ * topologies: one one-hop tree per rank, rank i the root of tree i, each tree
+ * carrying 1/k of the data (paper section 3.5). */
+#define BLINK_ROOT_ANY (-1)
+
+typedef enum {
+    BLINK_OK = 0,
+    BLINK_EINVAL = 1,        /* bad argument (null pointer, k < 2, bad vertex id, capacity <= 0, chunk 0, misaligned buffer ...) */
+    BLINK_EDISCONNECTED = 2, /* some vertex cannot be reached from the root: rate 0 */
+    BLINK_ENOMEM = 3,        /* host or device allocation failed */
+    BLINK_EMISMATCH = 4,     /* schedule does not fit the call (k, n, collective) */
+    BLINK_EHIP = 5           /* a HIP runtime call failed (no device, launch error) */
+} blink_status_t;
+
+typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
+typedef enum { BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1 } blink_op_t;
+typedef enum { BLINK_STEP_REDUCE = 0, BLINK_STEP_COPY = 1 } blink_step_kind_t;
+
+/* How many tree-edge transfers one workgroup carries a tile through before the
+ * data returns to HBM.  The result is bit-identical for all three.
+ *   EDGE  one transfer per step, as the paper issues them: a REDUCE reads both
+ *         rank buffers and writes the parent's, a COPY reads the parent's and
+ *         writes the child's; steps of one chunk hand over through device-side
+ *         completion counters.
+ *   NODE  the fan-in of one tree node (own data + all children) is one pass and
+ *         its fan-out (to all children) another; counters between nodes.  This
+ *         is what one GPU would do locally if every rank were its own GPU.
+ *   TREE  a tile is carried through all transfers of its tree at once: every
+ *         rank buffer is read once and written once; partial sums stay in LDS.
+ */
+typedef enum { BLINK_FUSE_EDGE = 0, BLINK_FUSE_NODE = 1, BLINK_FUSE_TREE = 2 } blink_fusion_t;
+
+typedef struct blink_trees blink_trees_t;
+typedef struct blink_schedule blink_schedule_t;
+
+/* One transfer over one tree edge for one chunk (paper section 4.1).
+ * REDUCE: dst[off, off+len) <- dst[off, off+len) + src[off, off+len)
+ * COPY:   dst[off, off+len) <- src[off, off+len)
+ * deps[0..n_deps) are indices of earlier steps of the list that must have
+ * completed before this one may start (the chunk-granular "event" of the
+ * paper). */
+typedef struct {
+    int32_t kind;    /* blink_step_kind_t */
+    int32_t tree;
+    int32_t chunk;   /* index of the chunk inside the tree's share */
+    int32_t src;     /* rank read */
+    int32_t dst;     /* rank written */
+    int32_t n_deps;  /* 0..2 */
+    int32_t deps[2];
+    uint64_t off;    /* first element */
+    uint64_t len;    /* elements */
+} blink_step_t;
+
+/* ---- tree packing (host only; no GPU needed) ------------------------------ */
+
+/* Pack spanning trees into a capacitated directed graph (section 3.1): k
+ * vertices, m arcs src[i] -> dst[i] of capacity cap[i] > 0 (all three: host
+ * arrays of length m; a bidirectional link is two arcs; parallel arcs add up).
+ * root in [0,k): multiplicative-weight-update fractional packing of
+ * arborescences rooted there (section 3.2, accuracy eps in (0, 0.5]), then
+ * reduced to few trees (section 3.2.1) accepting a rate loss of at most
+ * prune_tol in [0,1) against the MWU rate.  root == BLINK_ROOT_ANY: k one-hop
+ * trees (section 3.5); needs every arc i->j to be present, else BLINK_EINVAL.
+ * *out receives a new handle.  BLINK_EDISCONNECTED if a vertex is unreachable. */
+blink_status_t blink_pack_trees(int k, int m, const int32_t* src, const int32_t* dst,
+                                const double* cap, int root, double eps, double prune_tol,
+                                blink_trees_t** out);
+
+/* Wrap caller-chosen trees: roots[T], parent[T*k] (parent[t*k+v] is v's
+ * predecessor in tree t, -1 for the root), weight[T] > 0; host arrays.  Every
+ * tree must be a spanning arborescence of the complete graph on k vertices
+ * (no topology is checked here). */
+blink_status_t blink_trees_from_arrays(int k, int T, const int32_t* roots, const int32_t* parent,
+                                       const double* weight, blink_trees_t** out);
+
+int blink_trees_count(const blink_trees_t* trees);  /* T; -1 for a null handle */
+int blink_trees_k(const blink_trees_t* trees);      /* k; -1 for a null handle */
+double blink_trees_rate(const blink_trees_t* trees); /* sum of the weights */
+/* Tree t: *root, parent[k] (host, caller-allocated), *weight.  Any of the
+ * three output pointers may be null. */
+blink_status_t blink_trees_get(const blink_trees_t* trees, int t, int32_t* root,
+                               int32_t* parent, double* weight);
+void blink_trees_free(blink_trees_t* trees);
+
+/* ---- schedule (host only; no GPU needed) ------------------------------------ */
+
+/* Split [0, n_elems) among the trees in proportion to their weights (section
+ * 4.1): share boundaries are floor(n * prefix_weight / total_weight) rounded
+ * down to a multiple of 4 elements, exact in rational arithmetic.  Cut every
+ * share into chunks of chunk_elems (last one short, section 4.2.1).  Emit, per
+ * tree and chunk, one COPY per tree arc and (AllReduce) one REDUCE per reversed
+ * arc before them (section 3.3), with their dependencies, ordered so that all
+ * trees advance together, one chunk of each in turn (section 4.2.2).
+ * A node folds its children in ascending rank id (this fixes the fp32
+ * association order).  Broadcast needs all trees to share one root, else
+ * BLINK_EMISMATCH.  n_elems == 0 gives an empty, valid schedule. */
+blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, size_t n_elems,
+                                   size_t chunk_elems, blink_fusion_t fusion,
+                                   blink_schedule_t** out);
+
+size_t blink_schedule_num_steps(const blink_schedule_t* s);   /* tree-edge transfers */
+size_t blink_schedule_num_stages(const blink_schedule_t* s);  /* passes the kernel makes (== steps for EDGE) */
+int blink_schedule_num_trees(const blink_schedule_t* s);
+/* out[num_steps] (host, caller-allocated): the step list in execution order. */
+blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t* out);
+/* out[T+1] (host): share boundaries b_0 = 0 .. b_T = n_elems. */
+blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out);
+/* Bytes the kernel reads plus writes in rank buffers for one call with 4-byte
+ * elements, by construction of the stages (no cache effects). */
+uint64_t blink_schedule_traffic_bytes(const blink_schedule_t* s);
+void blink_schedule_free(blink_schedule_t* s);
+
+/* ---- execution (needs the GPU) -------------------------------------------------- */
+
+/* bufs: HOST array of k DEVICE pointers; each buffer holds at least n_elems
+ * 4-byte elements, is 16-byte aligned and overlaps no other.  In place.
+ * The call enqueues one kernel on `stream` (a hipStream_t passed as void*;
+ * null = the default stream) and returns without waiting; when the stream
+ * reaches the end of that kernel every bufs[i] holds the result:
+ *   allreduce: element j of every rank = sum over ranks of element j, added in
+ *              the order fixed by the tree that owns j (int32: modulo 2^32);
+ *   broadcast: every rank = the root's buffer.
+ * k, n_elems and the collective must be those the schedule was made for
+ * (BLINK_EMISMATCH otherwise).  The first call on a schedule also allocates
+ * and fills its small device-side tables (synchronously). */
+blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream);
+blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream);
+
+/* Launch shape override for tuning: workgroups per compute unit (0 = as many as
+ * fit) and 128-bit accesses per thread per buffer and tile (0 = automatic; 1, 2
+ * or 4).  Applies to later calls on this schedule. */
+blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int unroll);
+
+const char* blink_strerror(blink_status_t st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLINK_H */

@@ -1,0 +1,238 @@
+"""ctypes binding of libblink.so: the same names as include/blink.h, argument
+marshalling only.  Every step of the method runs inside the library.
+
+The library must have been built (``python -m paper_1910_04940_amd.build`` or
+``__graft_entry__.build()``); loading fails loudly otherwise.  There is no CPU
+fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libblink.so")
+
+BLINK_MAX_RANKS = 16
+BLINK_ROOT_ANY = -1
+BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP = range(6)
+BLINK_INT32, BLINK_FP32 = 0, 1
+BLINK_OP_BROADCAST, BLINK_OP_ALLREDUCE = 0, 1
+BLINK_STEP_REDUCE, BLINK_STEP_COPY = 0, 1
+BLINK_FUSE_EDGE, BLINK_FUSE_NODE, BLINK_FUSE_TREE = 0, 1, 2
+
+# numpy mirror of blink_step_t
+STEP_DTYPE = np.dtype([("kind", "<i4"), ("tree", "<i4"), ("chunk", "<i4"), ("src", "<i4"),
+                       ("dst", "<i4"), ("n_deps", "<i4"), ("deps", "<i4", (2,)),
+                       ("off", "<u8"), ("len", "<u8")], align=True)
+
+EXPORTS = [
+    "blink_pack_trees", "blink_trees_from_arrays", "blink_trees_count", "blink_trees_k",
+    "blink_trees_rate", "blink_trees_get", "blink_trees_free", "blink_make_schedule",
+    "blink_schedule_num_steps", "blink_schedule_num_stages", "blink_schedule_num_trees",
+    "blink_schedule_get_steps", "blink_schedule_get_bounds", "blink_schedule_traffic_bytes",
+    "blink_schedule_free", "blink_allreduce", "blink_broadcast", "blink_schedule_set_launch",
+    "blink_strerror",
+]
+
+
+class BlinkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first "
+                          "(python -m paper_1910_04940_amd.build); there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    i32p, f64p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_void_p
+    L.blink_pack_trees.argtypes = [C.c_int, C.c_int, i32p, i32p, f64p, C.c_int, C.c_double,
+                                   C.c_double, C.POINTER(vp)]
+    L.blink_trees_from_arrays.argtypes = [C.c_int, C.c_int, i32p, i32p, f64p, C.POINTER(vp)]
+    L.blink_trees_count.argtypes = [vp]
+    L.blink_trees_k.argtypes = [vp]
+    L.blink_trees_rate.argtypes = [vp]
+    L.blink_trees_rate.restype = C.c_double
+    L.blink_trees_get.argtypes = [vp, C.c_int, i32p, i32p, f64p]
+    L.blink_trees_free.argtypes = [vp]
+    L.blink_trees_free.restype = None
+    L.blink_make_schedule.argtypes = [vp, C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.POINTER(vp)]
+    L.blink_schedule_num_steps.argtypes = [vp]
+    L.blink_schedule_num_steps.restype = C.c_size_t
+    L.blink_schedule_num_stages.argtypes = [vp]
+    L.blink_schedule_num_stages.restype = C.c_size_t
+    L.blink_schedule_num_trees.argtypes = [vp]
+    L.blink_schedule_get_steps.argtypes = [vp, vp]
+    L.blink_schedule_get_bounds.argtypes = [vp, C.POINTER(C.c_uint64)]
+    L.blink_schedule_traffic_bytes.argtypes = [vp]
+    L.blink_schedule_traffic_bytes.restype = C.c_uint64
+    L.blink_schedule_free.argtypes = [vp]
+    L.blink_schedule_free.restype = None
+    for name in ("blink_allreduce", "blink_broadcast"):
+        getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, vp, vp]
+    L.blink_schedule_set_launch.argtypes = [vp, C.c_int, C.c_int]
+    L.blink_strerror.argtypes = [C.c_int]
+    L.blink_strerror.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return lib().blink_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != BLINK_OK:
+        raise BlinkError(status, where)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+class Trees:
+    """Owns a blink_trees_t handle."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.blink_trees_free(self._h)
+            self._h = None
+
+    @property
+    def count(self) -> int:
+        return lib().blink_trees_count(self._h)
+
+    @property
+    def k(self) -> int:
+        return lib().blink_trees_k(self._h)
+
+    @property
+    def rate(self) -> float:
+        return lib().blink_trees_rate(self._h)
+
+    def get(self, t: int) -> Tuple[int, Tuple[int, ...], float]:
+        root = C.c_int32()
+        weight = C.c_double()
+        parent = np.empty(self.k, np.int32)
+        _check(lib().blink_trees_get(self._h, t, C.byref(root), _ptr(parent, C.c_int32),
+                                     C.byref(weight)), "blink_trees_get")
+        return int(root.value), tuple(int(x) for x in parent), float(weight.value)
+
+    def as_lists(self):
+        """(roots, parent tuples, weights)."""
+        items = [self.get(t) for t in range(self.count)]
+        return [r for r, _, _ in items], [p for _, p, _ in items], [w for _, _, w in items]
+
+
+def blink_pack_trees(k: int, src, dst, cap, root: int, eps: float = 0.05,
+                     prune_tol: float = 0.05) -> Trees:
+    src, dst = _i32(src), _i32(dst)
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    if not (src.shape == dst.shape == cap.shape and src.ndim == 1):
+        raise ValueError("src, dst, cap must be 1-D arrays of one length")
+    out = C.c_void_p()
+    _check(lib().blink_pack_trees(k, src.shape[0], _ptr(src, C.c_int32), _ptr(dst, C.c_int32),
+                                  _ptr(cap, C.c_double), root, eps, prune_tol, C.byref(out)),
+           "blink_pack_trees")
+    return Trees(out.value)
+
+
+def blink_trees_from_arrays(k: int, roots, parents, weights) -> Trees:
+    roots = _i32(roots)
+    parents = _i32(parents).reshape(-1)
+    weights = np.ascontiguousarray(weights, dtype=np.float64)
+    T = roots.shape[0]
+    if parents.shape[0] != T * k or weights.shape[0] != T:
+        raise ValueError("parents must be T*k, weights T")
+    out = C.c_void_p()
+    _check(lib().blink_trees_from_arrays(k, T, _ptr(roots, C.c_int32), _ptr(parents, C.c_int32),
+                                         _ptr(weights, C.c_double), C.byref(out)),
+           "blink_trees_from_arrays")
+    return Trees(out.value)
+
+
+class Schedule:
+    """Owns a blink_schedule_t handle."""
+
+    def __init__(self, handle: int, k: int, n: int, op: int):
+        self._h = C.c_void_p(handle)
+        self.k, self.n, self.op = k, n, op
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.blink_schedule_free(self._h)
+            self._h = None
+
+    @property
+    def num_steps(self) -> int:
+        return lib().blink_schedule_num_steps(self._h)
+
+    @property
+    def num_stages(self) -> int:
+        return lib().blink_schedule_num_stages(self._h)
+
+    @property
+    def num_trees(self) -> int:
+        return lib().blink_schedule_num_trees(self._h)
+
+    @property
+    def traffic_bytes(self) -> int:
+        return lib().blink_schedule_traffic_bytes(self._h)
+
+    def steps(self) -> np.ndarray:
+        out = np.zeros(self.num_steps, STEP_DTYPE)
+        _check(lib().blink_schedule_get_steps(self._h, out.ctypes.data), "blink_schedule_get_steps")
+        return out
+
+    def bounds(self) -> List[int]:
+        out = np.zeros(self.num_trees + 1, np.uint64)
+        _check(lib().blink_schedule_get_bounds(self._h, _ptr(out, C.c_uint64)),
+               "blink_schedule_get_bounds")
+        return [int(x) for x in out]
+
+    def set_launch(self, wg_per_cu: int = 0, unroll: int = 0) -> None:
+        _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, unroll), "blink_schedule_set_launch")
+
+
+def blink_make_schedule(trees: Trees, op: int, n_elems: int, chunk_elems: int,
+                        fusion: int = BLINK_FUSE_TREE) -> Schedule:
+    out = C.c_void_p()
+    _check(lib().blink_make_schedule(trees._h, op, n_elems, chunk_elems, fusion, C.byref(out)),
+           "blink_make_schedule")
+    return Schedule(out.value, trees.k, n_elems, op)
+
+
+def _pointers(bufs: Sequence) -> "C.Array":
+    vals = [int(b.data_ptr()) if hasattr(b, "data_ptr") else int(b) for b in bufs]
+    return (C.c_void_p * len(vals))(*vals)
+
+
+def blink_allreduce(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:
+    """bufs: k device pointers (ints) or objects with .data_ptr(); stream: hipStream_t as int."""
+    arr = _pointers(bufs)
+    _check(lib().blink_allreduce(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
+           "blink_allreduce")
+
+
+def blink_broadcast(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:
+    arr = _pointers(bufs)
+    _check(lib().blink_broadcast(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
+           "blink_broadcast")

@@ -1,0 +1,172 @@
+// extern "C" boundary: argument checks, handle management, no exceptions out.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "state.hpp"
+#include "trees.hpp"
+
+using blink::Schedule;
+using blink::Trees;
+
+#define BLINK_GUARD_BEGIN try {
+#define BLINK_GUARD_END                 \
+    }                                   \
+    catch (const std::bad_alloc&) {     \
+        return BLINK_ENOMEM;            \
+    }                                   \
+    catch (...) {                       \
+        return BLINK_EINVAL;            \
+    }
+
+extern "C" {
+
+blink_status_t blink_pack_trees(int k, int m, const int32_t* src, const int32_t* dst,
+                                const double* cap, int root, double eps, double prune_tol,
+                                blink_trees_t** out) {
+    if (!out) return BLINK_EINVAL;
+    *out = nullptr;
+    BLINK_GUARD_BEGIN
+    blink_trees_t* h = new blink_trees_t();
+    const blink_status_t st = blink::pack_trees(k, m, src, dst, cap, root, eps, prune_tol, h->t);
+    if (st != BLINK_OK) {
+        delete h;
+        return st;
+    }
+    *out = h;
+    return BLINK_OK;
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_trees_from_arrays(int k, int T, const int32_t* roots, const int32_t* parent,
+                                       const double* weight, blink_trees_t** out) {
+    if (!out) return BLINK_EINVAL;
+    *out = nullptr;
+    if (k < 2 || k > BLINK_MAX_RANKS || T < 1 || !roots || !parent || !weight) return BLINK_EINVAL;
+    BLINK_GUARD_BEGIN
+    blink_trees_t* h = new blink_trees_t();
+    h->t.k = k;
+    for (int t = 0; t < T; ++t) {
+        blink::ParentVec p;
+        p.fill(-2);
+        bool ok = roots[t] >= 0 && roots[t] < k && weight[t] > 0.0 && std::isfinite(weight[t]);
+        for (int v = 0; ok && v < k; ++v) {
+            const int32_t q = parent[static_cast<size_t>(t) * k + v];
+            if (q < -1 || q >= k) ok = false;
+            p[v] = static_cast<int8_t>(q);
+        }
+        if (!ok || !blink::is_spanning_tree(k, roots[t], p)) {
+            delete h;
+            return BLINK_EINVAL;
+        }
+        h->t.root.push_back(roots[t]);
+        h->t.parent.push_back(p);
+        h->t.weight.push_back(weight[t]);
+    }
+    *out = h;
+    return BLINK_OK;
+    BLINK_GUARD_END
+}
+
+int blink_trees_count(const blink_trees_t* trees) { return trees ? trees->t.count() : -1; }
+int blink_trees_k(const blink_trees_t* trees) { return trees ? trees->t.k : -1; }
+
+double blink_trees_rate(const blink_trees_t* trees) {
+    if (!trees) return 0.0;
+    double r = 0.0;
+    for (double w : trees->t.weight) r += w;
+    return r;
+}
+
+blink_status_t blink_trees_get(const blink_trees_t* trees, int t, int32_t* root, int32_t* parent,
+                               double* weight) {
+    if (!trees || t < 0 || t >= trees->t.count()) return BLINK_EINVAL;
+    if (root) *root = trees->t.root[t];
+    if (parent)
+        for (int v = 0; v < trees->t.k; ++v) parent[v] = trees->t.parent[t][v];
+    if (weight) *weight = trees->t.weight[t];
+    return BLINK_OK;
+}
+
+void blink_trees_free(blink_trees_t* trees) { delete trees; }
+
+blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, size_t n_elems,
+                                   size_t chunk_elems, blink_fusion_t fusion,
+                                   blink_schedule_t** out) {
+    if (!out) return BLINK_EINVAL;
+    *out = nullptr;
+    if (!trees) return BLINK_EINVAL;
+    BLINK_GUARD_BEGIN
+    blink_schedule_t* h = new blink_schedule_t();
+    const blink_status_t st = blink::make_schedule(trees->t, op, n_elems, chunk_elems, fusion, h->s);
+    if (st != BLINK_OK) {
+        delete h;
+        return st;
+    }
+    *out = h;
+    return BLINK_OK;
+    BLINK_GUARD_END
+}
+
+size_t blink_schedule_num_steps(const blink_schedule_t* s) { return s ? s->s.steps.size() : 0; }
+size_t blink_schedule_num_stages(const blink_schedule_t* s) { return s ? s->s.inst.size() : 0; }
+int blink_schedule_num_trees(const blink_schedule_t* s) { return s ? s->s.n_trees : -1; }
+
+blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t* out) {
+    if (!s || (!out && !s->s.steps.empty())) return BLINK_EINVAL;
+    if (!s->s.steps.empty()) std::memcpy(out, s->s.steps.data(), s->s.steps.size() * sizeof(blink_step_t));
+    return BLINK_OK;
+}
+
+blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out) {
+    if (!s || !out) return BLINK_EINVAL;
+    for (size_t i = 0; i < s->s.bounds.size(); ++i) out[i] = s->s.bounds[i];
+    return BLINK_OK;
+}
+
+uint64_t blink_schedule_traffic_bytes(const blink_schedule_t* s) { return s ? s->s.traffic_bytes : 0; }
+
+void blink_schedule_free(blink_schedule_t* s) {
+    if (!s) return;
+    blink::release_device_state(s);
+    delete s;
+}
+
+blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_BROADCAST, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int unroll) {
+    if (!s || wg_per_cu < 0 || !(unroll == 0 || unroll == 1 || unroll == 2 || unroll == 4))
+        return BLINK_EINVAL;
+    s->wg_per_cu = wg_per_cu;
+    if (unroll != s->unroll) {
+        s->unroll = unroll;
+        return blink::reset_progress(s);
+    }
+    return BLINK_OK;
+}
+
+const char* blink_strerror(blink_status_t st) {
+    switch (st) {
+        case BLINK_OK: return "ok";
+        case BLINK_EINVAL: return "invalid argument";
+        case BLINK_EDISCONNECTED: return "a vertex is unreachable from the root";
+        case BLINK_ENOMEM: return "out of memory";
+        case BLINK_EMISMATCH: return "schedule does not match the call";
+        case BLINK_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+// From weighted trees to what the kernel consumes (paper sections 3.3, 4.1,
+// 4.2.1, 4.2.2): per-tree shares, chunks, the tree-edge step list, and the
+// "stages" (one or several steps carried out in a single pass over a tile).
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "trees.hpp"
+
+namespace blink {
+
+constexpr int kMaxOps = 40;    // micro-operations of one stage (<= 2k - 2 for k <= 16, see eval_tree)
+constexpr int kMaxDeps = 8;    // stages one stage may wait for
+
+// Micro-operations on the per-thread accumulator `acc` and the per-thread LDS
+// slots (slot i initially holds what was loaded from rank load_rank[i]).
+enum : uint8_t { OP_LD = 0, OP_ADD = 1, OP_ST = 2 };  // acc = slot; acc += slot; slot = acc
+inline uint8_t make_op(uint8_t kind, uint8_t slot) { return static_cast<uint8_t>((kind << 6) | slot); }
+
+// Shape of one stage, shared by all chunks of a tree.  Plain data: copied to the
+// device as is; the kernel reads it as 32-bit words and picks bytes out of them.
+struct alignas(4) StageTmpl {
+    uint8_t n_load, n_op, n_store, n_dep;
+    uint8_t signals;                 // some later stage waits for this one
+    uint8_t level;                   // length of the longest dependency chain below it
+    uint8_t pad[2];
+    uint8_t load_rank[BLINK_MAX_RANKS];
+    uint8_t store_rank[BLINK_MAX_RANKS];
+    uint8_t op[kMaxOps];
+    uint8_t dep_local[kMaxDeps];     // host only: index of the awaited stage among the tree's stages
+};
+
+// One stage applied to one chunk.  Plain data: copied to the device as is.
+struct StageInst {
+    uint64_t off;                    // first element
+    uint32_t len;                    // elements (a chunk is < 2^32 elements)
+    uint32_t tmpl;                   // index into the template table
+    uint32_t n_dep;
+    uint32_t pad;
+    int32_t dep[kMaxDeps];           // indices of earlier instances
+};
+static_assert(sizeof(StageTmpl) % 4 == 0, "StageTmpl is read as 32-bit words");
+
+struct Schedule {
+    int k = 0;
+    int n_trees = 0;
+    blink_op_t op = BLINK_OP_ALLREDUCE;
+    blink_fusion_t fusion = BLINK_FUSE_EDGE;
+    uint64_t n = 0, chunk = 0;
+    std::vector<uint64_t> bounds;        // T+1 share boundaries
+    std::vector<blink_step_t> steps;     // public tree-edge step list, execution order
+    std::vector<StageTmpl> tmpl;
+    std::vector<StageInst> inst;         // execution (ticket) order; dependencies point backwards
+    uint32_t max_slots = 1;              // largest n_load
+    uint64_t traffic_bytes = 0;
+};
+
+// Exact floor(n * (w_0+..+w_{t-1}) / (w_0+..+w_{T-1})) rounded down to a multiple of
+// `align`, made monotone; b_0 = 0, b_T = n.
+std::vector<uint64_t> split_by_weight(uint64_t n, const std::vector<double>& w, uint64_t align);
+
+blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint64_t chunk,
+                             blink_fusion_t fusion, Schedule& out);
+
+}  // namespace blink

@@ -1,0 +1,282 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, element
+by element on the same seeded inputs.  Bars: int32 and Broadcast bit-exact; fp32
+AllReduce max relative error <= 1e-6 against the oracle summing in the same tree
+order (0 is expected and also asserted)."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import execute as ox
+from oracle import graph as og
+from oracle import packing as op
+from oracle import schedule as osch
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_1910_04940_amd as bl  # noqa: E402
+
+FUSIONS = [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE]
+FP32_REL_TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    d = torch.device("cuda:0")
+    torch.cuda.set_device(d)
+    return d
+
+
+def pack(top, root):
+    return bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, root)
+
+
+def to_dev(arrs, dev):
+    return [torch.from_numpy(a).to(dev) for a in arrs]
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def assert_fp32_close_and_equal(got, want, label):
+    denom = np.maximum(np.abs(want), np.finfo(np.float32).tiny)
+    rel = np.max(np.abs(got.astype(np.float64) - want.astype(np.float64)) / denom) if want.size else 0.0
+    assert rel <= FP32_REL_TOL, f"{label}: max relative error {rel}"
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"{label}: not bit-identical"
+
+
+def run_allreduce_case(dev, top, root, n, chunk, dtype, fusion, seed, dist=None, scale=1.0,
+                       launch=None, calls=1):
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    dist = dist or ("int" if dtype == "int32" else "uniform")
+    x = [si.payload(seed, r, n, dist, dtype, scale) for r in range(top.k)]
+    want = [a.copy() for a in x]
+    steps = osch.make_steps(roots, parents, w, osch.ALLREDUCE, n, chunk)
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    if launch:
+        sched.set_launch(*launch)
+    code = bl.BLINK_INT32 if dtype == "int32" else bl.BLINK_FP32
+    for _ in range(calls):
+        bl.blink_allreduce(bufs, n, code, sched, stream())
+        ox.run_steps(want, steps)
+    torch.cuda.synchronize()
+    for r, (b, wv) in enumerate(zip(bufs, want)):
+        got = b.cpu().numpy()
+        label = f"{top.name} n={n} chunk={chunk} {dtype} fusion={fusion} rank={r}"
+        if dtype == "int32":
+            assert np.array_equal(got, wv), label
+        else:
+            assert_fp32_close_and_equal(got, wv, label)
+    if dtype == "int32" and calls == 1:
+        assert np.array_equal(want[0], ox.allreduce_int32_definition(x))
+
+
+TOPOLOGIES = [
+    (si.complete_graph(4), 0),
+    (si.hybrid_cube_mesh(), 0),
+    (si.hybrid_cube_mesh(doubled=True), 5),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (0, 1, 4)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (2, 3, 5, 6, 7)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (0, 1, 3, 4, 5, 7)), 0),
+    (si.chain(8), 0),
+    (si.star(7, 3), 3),
+    (si.complete_graph(2), 1),
+]
+
+
+@pytest.mark.parametrize("top,root", TOPOLOGIES)
+@pytest.mark.parametrize("fusion", FUSIONS)
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+def test_allreduce_matches_oracle(dev, top, root, fusion, dtype):
+    # several tiles per chunk, several chunks per tree, a ragged tail (n % 4 != 0)
+    run_allreduce_case(dev, top, root, n=300_003, chunk=20_000, dtype=dtype, fusion=fusion, seed=11)
+
+
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_config_k4_1m_fp32_chunk_64k(dev, fusion):
+    run_allreduce_case(dev, si.complete_graph(4), 0, n=1 << 20, chunk=1 << 16, dtype="fp32",
+                       fusion=fusion, seed=0)
+    run_allreduce_case(dev, si.complete_graph(4), 0, n=1 << 20, chunk=1 << 16, dtype="int32",
+                       fusion=fusion, seed=0)
+
+
+@pytest.mark.parametrize("n,chunk", [(1, 64), (3, 64), (4, 4), (5, 4), (17, 8), (1023, 1 << 20),
+                                     (4096, 1000), (4100, 1001), (100_000, 7), (8191, 8192),
+                                     (2048 * 8 + 4, 2048)])
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_small_ragged_and_misaligned_sizes(dev, n, chunk, fusion):
+    if chunk == 7 and n > 20_000:
+        n = 20_000      # element-wise path: keep the run short
+    for dtype in ("int32", "fp32"):
+        run_allreduce_case(dev, si.hybrid_cube_mesh(), 0, n=n, chunk=chunk, dtype=dtype,
+                           fusion=fusion, seed=n)
+
+
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_sixteen_rank_switch_one_hop_trees(dev, fusion):
+    top = si.complete_graph(16)
+    run_allreduce_case(dev, top, bl.BLINK_ROOT_ANY, n=16 * 5000 + 2, chunk=1024, dtype="fp32",
+                       fusion=fusion, seed=5)
+    run_allreduce_case(dev, top, bl.BLINK_ROOT_ANY, n=16 * 5000 + 2, chunk=1024, dtype="int32",
+                       fusion=fusion, seed=5)
+    run_allreduce_case(dev, top, 0, n=50_000, chunk=4096, dtype="fp32", fusion=fusion, seed=6)
+
+
+@pytest.mark.parametrize("fusion", FUSIONS)
+@pytest.mark.parametrize("launch", [(1, 1), (1, 2), (0, 1), (2, 0)])
+def test_launch_shapes_and_repeated_calls_on_one_schedule(dev, fusion, launch):
+    top = si.hybrid_cube_mesh()
+    if launch[1] == 2 and fusion == bl.BLINK_FUSE_TREE:
+        pass  # 8 ranks x unroll 2 = 16 columns: allowed
+    run_allreduce_case(dev, top, 0, n=200_000, chunk=16_384, dtype="int32", fusion=fusion,
+                       seed=21, launch=launch, calls=3)
+    run_allreduce_case(dev, top, 0, n=200_000, chunk=16_384, dtype="fp32", fusion=fusion,
+                       seed=22, dist="normal", scale=1e-3, launch=launch, calls=3)
+
+
+def test_gradient_like_values_and_denormals(dev):
+    # tiny magnitudes: subnormal partial sums must not be flushed
+    top = si.hybrid_cube_mesh()
+    run_allreduce_case(dev, top, 0, n=65_536, chunk=8192, dtype="fp32", fusion=bl.BLINK_FUSE_TREE,
+                       seed=31, dist="normal", scale=1e-39)
+    run_allreduce_case(dev, top, 0, n=65_536, chunk=8192, dtype="fp32", fusion=bl.BLINK_FUSE_EDGE,
+                       seed=31, dist="normal", scale=1e-39)
+
+
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_oracle_packed_trees_injected(dev, fusion):
+    """Trees chosen by the oracle's own packer, handed to the library as arrays."""
+    top = si.hybrid_cube_mesh(doubled=True)
+    roots, parents, w = op.pack_trees(og.Digraph.from_topology(top), 0)
+    trees = bl.blink_trees_from_arrays(top.k, roots, parents, w)
+    n, chunk = 123_457, 10_000
+    x = [si.payload(41, r, n, "uniform", "fp32") for r in range(top.k)]
+    want = [a.copy() for a in x]
+    ox.run_steps(want, osch.make_steps(roots, parents, w, osch.ALLREDUCE, n, chunk))
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert_fp32_close_and_equal(b.cpu().numpy(), want[0], "injected trees")
+    assert np.array_equal(want[0], ox.tree_order_allreduce(x, roots, parents, w))
+
+
+def test_uneven_weights(dev):
+    parents = [(-1, 0, 0, 1), (-1, 0, 1, 2), (-1, 3, 0, 0)]
+    w = [0.5, 1.25, 0.3]
+    trees = bl.blink_trees_from_arrays(4, [0, 0, 0], parents, w)
+    n, chunk = 99_999, 4096
+    for fusion in FUSIONS:
+        x = [si.payload(51, r, n, "uniform", "fp32") for r in range(4)]
+        want = [a.copy() for a in x]
+        ox.run_steps(want, osch.make_steps([0, 0, 0], parents, w, osch.ALLREDUCE, n, chunk))
+        bufs = to_dev(x, dev)
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+        bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+        torch.cuda.synchronize()
+        for b in bufs:
+            assert_fp32_close_and_equal(b.cpu().numpy(), want[0], f"uneven weights fusion {fusion}")
+
+
+# ---- Broadcast -----------------------------------------------------------------------
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.complete_graph(4), 2),
+                                      (si.chain(6), 5), (si.hybrid_cube_mesh(doubled=True), 3)])
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_broadcast_equals_root(dev, top, root, fusion):
+    n, chunk = 262_147, 16_384
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    x = [si.payload(61, r, n, "normal", "fp32") for r in range(top.k)]
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, n, chunk, fusion)
+    bl.blink_broadcast(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    want = ox.broadcast_definition(x, roots, w)
+    for b in bufs:
+        assert b.cpu().numpy().tobytes() == want.tobytes()
+    # int32 payloads through the same path
+    xi = [si.payload(62, r, n, "int", "int32") for r in range(top.k)]
+    bufs = to_dev(xi, dev)
+    bl.blink_broadcast(bufs, n, bl.BLINK_INT32, sched, stream())
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert np.array_equal(b.cpu().numpy(), xi[root])
+
+
+# ---- edge cases and errors ---------------------------------------------------------------
+def test_empty_payload_is_a_no_op(dev):
+    trees = pack(si.complete_graph(4), 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 0, 64)
+    bufs = [torch.zeros(4, device=dev) for _ in range(4)]
+    bl.blink_allreduce(bufs, 0, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+
+
+def test_untouched_memory_beyond_n(dev):
+    """The kernel writes elements [0, n) only."""
+    top = si.complete_graph(4)
+    n = 10_001
+    trees = pack(top, 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, 2048)
+    bufs = [torch.full((n + 64,), 7.0, device=dev) for _ in range(4)]
+    bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert (b[n:] == 7.0).all() and (b[:n] == 28.0).all()
+
+
+def test_call_errors(dev):
+    top = si.complete_graph(4)
+    n = 4096
+    trees = pack(top, 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, 1024)
+    bufs = [torch.zeros(n + 4, device=dev) for _ in range(4)]
+
+    def status(fn, *a):
+        with pytest.raises(bl.BlinkError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(bl.blink_allreduce, bufs[:3], n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EMISMATCH
+    assert status(bl.blink_allreduce, bufs, n - 1, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EMISMATCH
+    assert status(bl.blink_broadcast, bufs, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EMISMATCH
+    assert status(bl.blink_allreduce, bufs, n, 5, sched, stream()) == bl.BLINK_EINVAL
+    mis = [bufs[0].data_ptr() + 4] + [b.data_ptr() for b in bufs[1:]]
+    assert status(bl.blink_allreduce, mis, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EINVAL
+    ovl = [bufs[0].data_ptr(), bufs[0].data_ptr() + 16] + [b.data_ptr() for b in bufs[2:]]
+    assert status(bl.blink_allreduce, ovl, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EINVAL
+    null = [0] + [b.data_ptr() for b in bufs[1:]]
+    assert status(bl.blink_allreduce, null, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EINVAL
+    assert status(sched.set_launch, 0, 3) == bl.BLINK_EINVAL
+    # 16 ranks read at once leave room for one 128-bit column per thread only
+    t16 = pack(si.complete_graph(16), bl.BLINK_ROOT_ANY)
+    s16 = bl.blink_make_schedule(t16, bl.BLINK_OP_ALLREDUCE, 1 << 16, 4096, bl.BLINK_FUSE_TREE)
+    s16.set_launch(0, 2)
+    b16 = [torch.zeros(1 << 16, device=dev) for _ in range(16)]
+    assert status(bl.blink_allreduce, b16, 1 << 16, bl.BLINK_FP32, s16, stream()) == bl.BLINK_EINVAL
+    # the schedule still works after all those refusals
+    bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+
+
+def test_non_default_stream(dev):
+    top = si.hybrid_cube_mesh()
+    n, chunk = 150_000, 8192
+    trees = pack(top, 0)
+    roots, parents, w = trees.as_lists()
+    x = [si.payload(71, r, n, "int", "int32") for r in range(8)]
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_EDGE)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, s.cuda_stream)
+    s.synchronize()
+    want = ox.allreduce_int32_definition(x)
+    for b in bufs:
+        assert np.array_equal(b.cpu().numpy(), want)

@@ -1,0 +1,227 @@
+"""Host-side logic of the HIP library through its C ABI (no GPU, no kernels):
+tree packing and scheduling, judged by the oracle's validators."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1910_04940_amd as bl
+import synth_inputs as si
+from oracle import graph as og
+from oracle import packing as op
+from oracle import schedule as osch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def pack(top, root, **kw):
+    return bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, root, **kw)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "blink.h")).read()
+    declared = set(re.findall(r"\b(blink_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 19
+    from paper_1910_04940_amd import binding
+    lib = binding.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+# ---- packing ---------------------------------------------------------------------
+PACK_CASES = [
+    (si.complete_graph(4), 0),
+    (si.complete_graph(8), 5),
+    (si.hybrid_cube_mesh(), 0),
+    (si.hybrid_cube_mesh(), 6),
+    (si.hybrid_cube_mesh(doubled=True), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (0, 1, 4)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (2, 3, 5, 6, 7)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (0, 1, 3, 4, 5, 7)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (1, 4, 5, 6)), 0),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (2, 3, 6, 7)), 0),
+    (si.chain(7, 2.0), 3),
+    (si.star(6, 2), 2),
+    (si.ring(6), 0),
+]
+
+
+@pytest.mark.parametrize("top,root", PACK_CASES)
+def test_integer_graphs_reach_the_min_root_cut_with_few_trees(top, root):
+    g = og.Digraph.from_topology(top)
+    lam = og.min_root_cut(g, root)
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    rate = op.check_packing(g, roots, parents, w)
+    assert rate == pytest.approx(trees.rate)
+    assert rate == lam                      # Edmonds: integral capacities pack exactly
+    assert trees.count <= lam               # no more trees than units of rate
+    assert all(r == root for r in roots)
+
+
+def test_dgx1v_graph_gives_six_unit_trees(paper_pins):
+    trees = pack(si.hybrid_cube_mesh(doubled=True), 0)
+    assert trees.count == int(paper_pins["dgx1v_pruned_tree_count"])
+    assert all(w == float(paper_pins["dgx1v_pruned_tree_rate"]) for w in trees.as_lists()[2])
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_fractional_graphs_feasible_and_near_optimal(seed):
+    top = si.random_digraph(5 + seed % 4, 0.45, 500 + seed, int_caps=False)
+    g = og.Digraph.from_topology(top)
+    lam = og.min_root_cut(g, 0)
+    eps, tol = 0.05, 0.05
+    trees = pack(top, 0, eps=eps, prune_tol=tol)
+    roots, parents, w = trees.as_lists()
+    rate = op.check_packing(g, roots, parents, w)
+    assert rate <= lam + 1e-9
+    assert rate >= (1 - tol) * (1 - 2 * eps) * lam
+
+
+def test_parallel_arcs_add_up():
+    src = np.array([0, 0, 1, 1], np.int32)
+    dst = np.array([1, 1, 0, 0], np.int32)
+    cap = np.array([1.0, 1.0, 1.0, 1.0])
+    trees = bl.blink_pack_trees(2, src, dst, cap, 0)
+    assert trees.count == 1 and trees.rate == 2.0
+
+
+def test_one_hop_trees_for_switch_topologies():
+    top = si.complete_graph(16)
+    trees = pack(top, bl.BLINK_ROOT_ANY)
+    roots, parents, w = trees.as_lists()
+    oroots, otrees, ow = op.one_hop_stars(og.Digraph.from_topology(top))
+    assert roots == oroots and parents == otrees and w == ow
+    with pytest.raises(bl.BlinkError) as e:
+        pack(si.chain(4), bl.BLINK_ROOT_ANY)
+    assert e.value.status == bl.BLINK_EINVAL
+
+
+def test_pack_error_codes():
+    top = si.complete_graph(4)
+    bad = [
+        dict(k=1), dict(k=17), dict(root=4), dict(root=-2), dict(eps=0.0), dict(eps=0.9),
+        dict(prune_tol=1.0), dict(prune_tol=-0.1),
+    ]
+    for kw in bad:
+        args = dict(k=top.k, src=top.src, dst=top.dst, cap=top.cap, root=0, eps=0.05, prune_tol=0.05)
+        args.update(kw)
+        with pytest.raises(bl.BlinkError) as e:
+            bl.blink_pack_trees(**args)
+        assert e.value.status == bl.BLINK_EINVAL, kw
+    for src, dst, cap in [([0, 5], [1, 0], [1, 1]), ([0, 1], [1, 1], [1, 1]), ([0, 1], [1, 0], [1, 0]),
+                          ([0, 1], [1, 0], [1, -1]), ([0, 1], [1, 0], [1, float("nan")])]:
+        with pytest.raises(bl.BlinkError) as e:
+            bl.blink_pack_trees(2, src, dst, cap, 0)
+        assert e.value.status == bl.BLINK_EINVAL
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_pack_trees(3, [0, 2], [1, 1], [1.0, 1.0], 0)       # vertex 2 unreachable
+    assert e.value.status == bl.BLINK_EDISCONNECTED
+    assert "unreachable" in bl.strerror(bl.BLINK_EDISCONNECTED)
+
+
+def test_trees_from_arrays_round_trip_and_rejects_non_trees():
+    roots, parents, w = op.pack_trees(og.Digraph.from_topology(si.hybrid_cube_mesh()), 0)
+    t = bl.blink_trees_from_arrays(8, roots, parents, w)
+    assert t.as_lists() == (roots, parents, w) and t.k == 8 and t.rate == sum(w)
+    for bad in [(-1, 2, 1), (-1, 0, 3), (0, 0, 1), (-1, -1, 0)]:
+        with pytest.raises(bl.BlinkError):
+            bl.blink_trees_from_arrays(3, [0], [bad], [1.0])
+    with pytest.raises(bl.BlinkError):
+        bl.blink_trees_from_arrays(3, [0], [(-1, 0, 1)], [0.0])
+
+
+# ---- schedule ------------------------------------------------------------------------
+def to_oracle_steps(sched):
+    return [osch.Step(int(s["kind"]), int(s["tree"]), int(s["chunk"]), int(s["src"]), int(s["dst"]),
+                      int(s["off"]), int(s["len"]), tuple(int(d) for d in s["deps"][:int(s["n_deps"])]))
+            for s in sched.steps()]
+
+
+SCHED_CASES = [
+    (si.complete_graph(4), 0, 1 << 20, 1 << 16),
+    (si.hybrid_cube_mesh(), 0, 300_001, 8192),
+    (si.hybrid_cube_mesh(doubled=True), 2, 77_777, 5000),
+    (si.induced(si.hybrid_cube_mesh(doubled=True), (2, 3, 5, 6, 7)), 0, 65_536, 65_536),
+    (si.chain(6), 0, 10_000, 999),
+    (si.star(5, 3), 3, 1000, 64),
+    (si.complete_graph(4), 0, 3, 64),
+]
+
+
+@pytest.mark.parametrize("top,root,n,chunk", SCHED_CASES)
+@pytest.mark.parametrize("coll", [bl.BLINK_OP_ALLREDUCE, bl.BLINK_OP_BROADCAST])
+@pytest.mark.parametrize("fusion", [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE])
+def test_schedule_passes_oracle_validators(top, root, n, chunk, coll, fusion):
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    sched = bl.blink_make_schedule(trees, coll, n, chunk, fusion)
+    assert sched.bounds() == osch.split_by_weight(n, w)
+    steps = to_oracle_steps(sched)
+    ocoll = osch.ALLREDUCE if coll == bl.BLINK_OP_ALLREDUCE else osch.BROADCAST
+    osch.check_steps(steps, top.k, roots, parents, w, ocoll, n, chunk)
+    assert len(steps) == len(osch.make_steps(roots, parents, w, ocoll, n, chunk))
+    # analytic traffic of the three fusion levels (4-byte elements)
+    k = top.k
+    if fusion == bl.BLINK_FUSE_EDGE:
+        per = 20 * (k - 1) if coll == bl.BLINK_OP_ALLREDUCE else 8 * (k - 1)
+        assert sched.traffic_bytes == per * n and sched.num_stages == len(steps)
+    if fusion == bl.BLINK_FUSE_TREE:
+        per = 8 * k if coll == bl.BLINK_OP_ALLREDUCE else 4 * k
+        assert sched.traffic_bytes == per * n
+        assert sched.num_stages == len({(s.tree, s.chunk) for s in steps})
+    if fusion == bl.BLINK_FUSE_NODE:
+        b = sched.bounds()
+        want = 0
+        for t, parent in enumerate(parents):
+            internal = len({p for p in parent if p >= 0})
+            per = 4 * (2 * (k - 1) + 3 * internal - 1) if coll == bl.BLINK_OP_ALLREDUCE else 4 * (internal + k - 1)
+            want += per * (b[t + 1] - b[t])
+        assert sched.traffic_bytes == want
+
+
+def test_trees_advance_together_in_the_step_order():
+    """Fair interleaving (section 4.2.2): in execution order no tree is ever more
+    than one pipeline slot ahead of another."""
+    trees = pack(si.hybrid_cube_mesh(), 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, 1 << 22, 1 << 16, bl.BLINK_FUSE_EDGE)
+    seen = {}
+    for s in sched.steps():
+        seen[int(s["tree"])] = int(s["chunk"])
+        if len(seen) == trees.count:
+            assert max(seen.values()) - min(seen.values()) <= 4   # tree height bounds the skew
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, 1 << 22, 1 << 16, bl.BLINK_FUSE_TREE)
+    # fully fused: stage i belongs to tree i mod T
+    assert sched.num_stages == trees.count * 16
+
+
+@pytest.mark.parametrize("weights", [[1.0, 1.0, 1.0], [0.3, 0.7], [1e-9, 1.0, 3.0], [0.1] * 7,
+                                     [2.0 ** -40, 2.0 ** 40], [1 / 3, 1 / 7, 1 / 11, 0.5]])
+@pytest.mark.parametrize("n", [0, 1, 5, 4096, 1_000_003, (1 << 40) + 12345])
+def test_exact_weighted_split_matches_rational_arithmetic(weights, n):
+    T = len(weights)
+    parents = [(-1, 0)] * T
+    trees = bl.blink_trees_from_arrays(2, [0] * T, parents, weights)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, n, 1 << 30, bl.BLINK_FUSE_TREE)
+    b = sched.bounds()
+    assert b == osch.split_by_weight(n, weights)
+    osch.check_split(b, n, weights)
+
+
+def test_schedule_error_codes():
+    trees = pack(si.complete_graph(4), 0)
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 100, 0)
+    assert e.value.status == bl.BLINK_EINVAL
+    with pytest.raises(bl.BlinkError):
+        bl.blink_make_schedule(trees, 7, 100, 10)
+    with pytest.raises(bl.BlinkError):
+        bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 100, 10, 9)
+    stars = pack(si.complete_graph(4), bl.BLINK_ROOT_ANY)
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_make_schedule(stars, bl.BLINK_OP_BROADCAST, 100, 10)   # several roots
+    assert e.value.status == bl.BLINK_EMISMATCH
+    empty = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 0, 64)
+    assert empty.num_steps == 0 and empty.num_stages == 0 and empty.traffic_bytes == 0
