@@ -8,6 +8,7 @@ fallback.
 from __future__ import annotations
 
 import ctypes as C
+import importlib.util
 import os
 from typing import List, Sequence, Tuple
 
@@ -46,6 +47,32 @@ class BlinkError(RuntimeError):
 
 
 _lib = None
+_hip = None
+
+
+def _load_hip_runtime() -> None:
+    """libblink.so leaves the HIP entry points undefined so that it binds to the
+    one HIP runtime of the process.  PyTorch wheels bundle their own
+    libamdhip64; device memory and streams come from PyTorch, so that copy is
+    the one to share.  Without PyTorch the system ROCm runtime is used."""
+    global _hip
+    if _hip is not None:
+        return
+    candidates = []
+    spec = importlib.util.find_spec("torch")
+    if spec is not None and spec.origin:
+        candidates.append(os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so"))
+    candidates += ["/opt/rocm/lib/libamdhip64.so", "libamdhip64.so"]
+    errors = []
+    for path in candidates:
+        if os.path.isabs(path) and not os.path.exists(path):
+            continue
+        try:
+            _hip = C.CDLL(path, mode=C.RTLD_GLOBAL)
+            return
+        except OSError as e:  # try the next candidate
+            errors.append(f"{path}: {e}")
+    raise ImportError("no HIP runtime could be loaded: " + "; ".join(errors))
 
 
 def lib() -> C.CDLL:
@@ -55,6 +82,7 @@ def lib() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first "
                           "(python -m paper_1910_04940_amd.build); there is no fallback path")
+    _load_hip_runtime()
     L = C.CDLL(LIB_PATH)
     i32p, f64p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_void_p
     L.blink_pack_trees.argtypes = [C.c_int, C.c_int, i32p, i32p, f64p, C.c_int, C.c_double,

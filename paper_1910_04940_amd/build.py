@@ -1,4 +1,10 @@
-"""Compile the HIP library in-tree: csrc/* -> libblink.so (gfx950 only)."""
+"""Compile the HIP library in-tree: csrc/* -> libblink.so (gfx950 only).
+
+The objects are linked WITHOUT a dependency on a particular libamdhip64: a
+process must hold exactly one HIP runtime, and a PyTorch wheel brings its own.
+The HIP entry points are therefore left undefined and bind, at load time, to
+the runtime the process has already loaded (binding.py sees to that; a C or
+C++ program simply links its own libamdhip64)."""
 import os
 import subprocess
 import sys
@@ -8,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libblink.so")
 SOURCES = ["api.cpp", "pack.cpp", "schedule.cpp", "exec.hip"]
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-c",
     "-fno-gpu-flush-denormals-to-zero",      # fp32 subnormals are ordinary addends
     "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -18,13 +24,20 @@ FLAGS = [
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = []
     for s in SOURCES:
-        cmd += (["-x", "hip"] if s.endswith(".cpp") else []) + [os.path.join(CSRC, s)]
-    cmd += ["-o", LIB]
+        obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
+        cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True, stderr=None if verbose else subprocess.DEVNULL)
+        objs.append(obj)
+    link = [os.environ.get("CXX", "g++"), "-shared", "-o", LIB] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 

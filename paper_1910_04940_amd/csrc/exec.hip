@@ -1,21 +1,22 @@
 // The device side: one persistent gfx950 kernel that consumes the stage list of
 // all trees concurrently (paper sections 3.3, 4.1, 4.2.1, 4.2.2), and its launcher.
 //
-// Work unit: (stage instance, tile).  Workgroups draw units from one ticket
-// counter in the schedule's execution order, so every unit a workgroup might
-// have to wait for has already been drawn by a workgroup that is running:
-// waiting can never deadlock, whatever the grid size.
+// A workgroup is ONE 64-lane wavefront: nothing in the kernel needs a
+// workgroup barrier, and a wave that waits for a dependency holds up nobody
+// else.  Work unit: (stage instance, tile).  Waves draw units from one ticket
+// counter in the schedule's execution order, so every unit a wave might have
+// to wait for has already been drawn by a wave that is running: waiting can
+// never deadlock, whatever the grid size.
 //
-// A tile of a stage is processed in three phases by 256 threads, each owning
-// U 128-bit columns:
-//   1. load the tile from every rank the stage reads; all loads are issued
-//      before the first is consumed, then parked in per-thread LDS slots;
+// A tile is kSub sub-tiles; a sub-tile of a stage is processed in three phases
+// by the 64 lanes, each owning U 128-bit columns:
+//   1. load the sub-tile from every rank the stage reads; all loads are issued
+//      before the first is consumed, then parked in per-lane LDS slots;
 //   2. run the stage's micro-program (acc = slot / acc += slot / slot = acc)
 //      over the slots: this is where the tree's summation order is applied,
 //      with partial sums staged in LDS instead of going back to HBM;
 //   3. store acc to every rank the stage writes.
-// LDS slots are private to a thread (thread t only touches column t), so no
-// barrier is needed inside a tile.
+// LDS slots are private to a lane (lane l only touches column l).
 //
 // Chunk-granular hand-over (the paper's per-chunk event): a stage instance has
 // a 64-bit counter of finished tiles.  Counters are never reset; call number e
@@ -33,8 +34,9 @@
 
 namespace blink {
 
-constexpr int kThreads = 256;
-// 128-bit columns a thread may hold in registers at once (ranks read x unroll):
+constexpr int kLanes = 64;   // one wavefront per workgroup
+constexpr int kSub = 4;      // sub-tiles per ticket
+// 128-bit columns a lane may hold in registers at once (ranks read x unroll):
 // keeps the load phase inside the register file.
 constexpr int kMaxColumns = 16;
 
@@ -89,16 +91,16 @@ __device__ __forceinline__ void load_slots_full(V* __restrict__ slots, ConstPara
     for (int i = 0; i < NL; ++i) {
         const BLINK_GLOBAL V* src = rank_ptr<V>(p, BLINK_TMPL(st, load_rank, i), byte_off);
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[i][u] = src[u * kThreads + tid];
+        for (int u = 0; u < U; ++u) r[i][u] = src[u * kLanes + tid];
     }
 #pragma unroll
     for (int i = 0; i < NL; ++i)
 #pragma unroll
-        for (int u = 0; u < U; ++u) slots[(i * U + u) * kThreads + tid] = r[i][u];
+        for (int u = 0; u < U; ++u) slots[(i * U + u) * kLanes + tid] = r[i][u];
 }
 
 // Phases 1-3 for `nvec` elements of type V starting at byte_off.  FULL: the
-// tile has all kThreads*U elements (the common case, no per-lane guards).
+// tile has all kLanes*U elements (the common case, no per-lane guards).
 template <typename V, int U, bool FULL>
 __device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, ConstTmpl st,
                                          unsigned long long byte_off, unsigned nvec, int tid) {
@@ -121,8 +123,8 @@ __device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, C
             const BLINK_GLOBAL V* src = rank_ptr<V>(p, BLINK_TMPL(st, load_rank, i), byte_off);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const unsigned idx = u * kThreads + tid;
-                if (idx < nvec) slots[(i * U + u) * kThreads + tid] = src[idx];
+                const unsigned idx = u * kLanes + tid;
+                if (idx < nvec) slots[(i * U + u) * kLanes + tid] = src[idx];
             }
         }
     }
@@ -130,17 +132,17 @@ __device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, C
     const int n_op = BLINK_TMPL(st, n_op, 0);
     for (int o = 0; o < n_op; ++o) {
         const unsigned code = BLINK_TMPL(st, op, o);
-        V* sl = slots + (code & 63u) * (U * kThreads) + tid;
+        V* sl = slots + (code & 63u) * (U * kLanes) + tid;
         const unsigned kind = code >> 6;
         if (kind == OP_LD) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = sl[u * kThreads];
+            for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
         } else if (kind == OP_ADD) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = vadd(acc[u], sl[u * kThreads]);
+            for (int u = 0; u < U; ++u) acc[u] = vadd(acc[u], sl[u * kLanes]);
         } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) sl[u * kThreads] = acc[u];
+            for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
         }
     }
     const int n_store = BLINK_TMPL(st, n_store, 0);
@@ -148,7 +150,7 @@ __device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, C
         BLINK_GLOBAL V* dst = rank_ptr<V>(p, BLINK_TMPL(st, store_rank, j), byte_off);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const unsigned idx = u * kThreads + tid;
+            const unsigned idx = u * kLanes + tid;
             if (FULL || idx < nvec) dst[idx] = acc[u];
         }
     }
@@ -158,11 +160,11 @@ __device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, C
 // The by-value argument is only there to size the kernel-argument segment; it is
 // read through the constant address space (see ConstParams).
 template <typename T, typename V4, int U>
-__global__ __launch_bounds__(kThreads) void blink_consume(const KParams) {
+__global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    __shared__ unsigned long long s_ticket;
-    const int tid = threadIdx.x;
-    constexpr unsigned kTile = kThreads * 4 * U;  // elements per tile
+    const int lane = threadIdx.x;
+    constexpr unsigned kSubTile = kLanes * 4 * U;   // elements per sub-tile
+    constexpr unsigned kTile = kSubTile * kSub;     // elements per ticket
     ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
     unsigned long long* const ticket = p->ticket;
     unsigned long long* const done = p->done;
@@ -170,13 +172,21 @@ __global__ __launch_bounds__(kThreads) void blink_consume(const KParams) {
     ConstInst const inst = reinterpret_cast<ConstInst>(reinterpret_cast<unsigned long long>(p->inst));
     const unsigned long long n_items = p->n_items, ticket_base = p->ticket_base, epoch = p->epoch;
     const unsigned tiles_per_chunk = p->tiles_per_chunk;
+    V4* const slots = reinterpret_cast<V4*>(lds_raw);
 
+    // The loop has exactly one lane-dependent region, at its head, and one back
+    // edge: the compiler must never get the chance to let some lanes run ahead
+    // of lane 0 around the loop (readfirstlane needs lane 0 present).  Hence the
+    // completion signal of a tile is posted together with the next ticket draw.
+    long long pending = -1;  // instance whose finished tile still has to be counted
     for (;;) {
-        if (tid == 0)
-            s_ticket = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        const unsigned long long raw = s_ticket - ticket_base;
-        __syncthreads();
+        unsigned long long raw = 0;
+        if (lane == 0) {
+            if (pending >= 0)
+                __hip_atomic_fetch_add(done + pending, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            raw = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ticket_base;
+        }
+        pending = -1;
         const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw));
         const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw >> 32));
         const unsigned long long t = (static_cast<unsigned long long>(hi) << 32) | lo;
@@ -186,48 +196,41 @@ __global__ __launch_bounds__(kThreads) void blink_consume(const KParams) {
         ConstInst in = inst + ii;
         const unsigned len = in->len;
         const unsigned long long tile_off = static_cast<unsigned long long>(tile) * kTile;
-        if (tile_off >= len) continue;
-        const unsigned tlen = min(kTile, static_cast<unsigned>(len - tile_off));
-        ConstTmpl st = tmpl + in->tmpl;
+        if (tile_off < len) {  // a short last chunk has fewer tiles than tickets
+            const unsigned tlen = min(kTile, static_cast<unsigned>(len - tile_off));
+            ConstTmpl st = tmpl + in->tmpl;
 
-        const int n_dep = in->n_dep;
-        if (n_dep) {
-            if (tid < n_dep) {
-                const unsigned long long want = epoch * ((len + kTile - 1) / kTile);
-                const unsigned long long* f = done + in->dep[tid];
-                while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want)
-                    __builtin_amdgcn_s_sleep(2);
+            const int n_dep = in->n_dep;
+            if (n_dep) {
+                if (lane < n_dep) {
+                    const unsigned long long want = epoch * ((len + kTile - 1) / kTile);
+                    const unsigned long long* f = done + in->dep[lane];
+                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want)
+                        __builtin_amdgcn_s_sleep(2);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            __syncthreads();
-        }
 
-        const unsigned long long e0 = in->off + tile_off;  // first element of the tile
-        if ((e0 & 3ull) == 0) {
-            V4* slots = reinterpret_cast<V4*>(lds_raw);
-            const unsigned nvec = tlen >> 2;
-            if (nvec == kThreads * U)
-                run_tile<V4, U, true>(slots, p, st, e0 * 4ull, nvec, tid);
-            else if (nvec)
-                run_tile<V4, U, false>(slots, p, st, e0 * 4ull, nvec, tid);
-            const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
-            if (rem) {
-                __syncthreads();  // the scalar columns overlay other threads' vector columns
-                run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + (nvec << 2)) * 4ull, rem, tid);
+            const unsigned long long e0 = in->off + tile_off;  // first element of the tile
+            if ((e0 & 3ull) == 0) {
+                const unsigned nvec = tlen >> 2;
+                unsigned v = 0;
+                for (; v + kLanes * U <= nvec; v += kLanes * U)
+                    run_tile<V4, U, true>(slots, p, st, (e0 + 4ull * v) * 4ull, kLanes * U, lane);
+                if (v < nvec) run_tile<V4, U, false>(slots, p, st, (e0 + 4ull * v) * 4ull, nvec - v, lane);
+                const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
+                if (rem)
+                    run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + (nvec << 2)) * 4ull, rem, lane);
+            } else {
+                // chunk size not a multiple of 4 elements: element-wise, slow but correct
+                for (unsigned done_e = 0; done_e < tlen; done_e += kLanes)
+                    run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + done_e) * 4ull,
+                                          min(static_cast<unsigned>(kLanes), tlen - done_e), lane);
             }
-        } else {
-            // chunk size not a multiple of 4 elements: element-wise, slow but correct
-            for (unsigned done_e = 0; done_e < tlen; done_e += kThreads)
-                run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + done_e) * 4ull,
-                                      min(static_cast<unsigned>(kThreads), tlen - done_e), tid);
-        }
 
-        if (BLINK_TMPL(st, signals, 0)) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            __syncthreads();
-            if (tid == 0) {
+            if (BLINK_TMPL(st, signals, 0)) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                __hip_atomic_fetch_add(done + ii, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pending = ii;
             }
         }
     }
@@ -320,18 +323,18 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
 
     int unroll = h->unroll;
     if (unroll == 0) unroll = s.max_slots <= 4 ? 4 : (s.max_slots <= 8 ? 2 : 1);
-    const unsigned tile = kThreads * 4 * unroll;
+    const unsigned tile = kLanes * 4 * unroll * kSub;
     uint32_t longest = 0;
     for (const StageInst& in : s.inst) longest = std::max(longest, in.len);
     const unsigned tiles_per_chunk = (longest + tile - 1) / tile;
     const unsigned long long n_items = static_cast<unsigned long long>(s.inst.size()) * tiles_per_chunk;
     if (static_cast<int>(s.max_slots) * unroll > kMaxColumns) return BLINK_EINVAL;
-    const size_t lds = static_cast<size_t>(s.max_slots) * unroll * kThreads * 16;
+    const size_t lds = static_cast<size_t>(s.max_slots) * unroll * kLanes * 16;
 
     KernelFn fn = pick_kernel(dtype, unroll);
     int& cached = h->occupancy[dtype == BLINK_FP32][unroll == 1 ? 0 : (unroll == 2 ? 1 : 2)];
     if (cached == 0) {
-        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kThreads, lds));
+        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, lds));
         if (cached < 1) {
             cached = 0;
             return BLINK_EHIP;
@@ -352,7 +355,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.n_items = n_items;
     p.epoch = ++h->epoch;
     p.tiles_per_chunk = tiles_per_chunk;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kThreads), lds,
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), lds,
                        static_cast<hipStream_t>(stream), p);
     BLINK_HIP(hipGetLastError());
     h->ticket_base += n_items + grid;  // every workgroup draws exactly one ticket past the end
