@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed-tree AllReduce hot path on one MI355X.
+
+A "step" is one blink_allreduce call over the headline workload: 8 virtual
+ranks (8 HBM buffers on the one GPU) on the unit-capacity hybrid cube-mesh,
+67,108,864 fp32 per rank (256 MiB), 4 packed unit-weight trees, 1 MiB chunks.
+Inputs are resident in HBM before the timed region; the schedule is built once
+outside it (the paper reuses its generated code across iterations).
+
+Prints ONE JSON line.  value = algorithm GB/s = per-rank payload bytes / time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "AllReduce alg GB/s + achieved HBM GB/s vs peak, 8 ranks, 256 MB fp32"
+HBM_PEAK_GBS = 8000.0
+# Per call the input of step i+1 is the output of step i (in place), so values grow
+# by a factor k per step; buffers are restored from a pristine copy before they
+# could overflow.  The restore is a plain device copy inside the timed bracket
+# (it only makes the reported number slightly pessimistic) and is counted.
+MAX_STEPS_BETWEEN_RESTORES = 32
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--fusion", choices=["edge", "node", "tree"], default="tree")
+    ap.add_argument("--chunk-bytes", type=int, default=1 << 20)
+    ap.add_argument("--elems", type=int, default=1 << 26, help="fp32 elements per rank")
+    ap.add_argument("--dtype", choices=["fp32", "int32"], default="fp32")
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--check", action="store_true", help="verify sampled outputs against the oracle")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark, run a plain device copy of known size "
+                         "(reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
+    return ap.parse_args()
+
+
+def calibrate_copy(steps):
+    """A plain 1 GiB device-to-device copy (torch's copy kernel), `steps` times:
+    reads 2^30 bytes and writes 2^30 bytes per launch."""
+    import torch
+    torch.cuda.set_device(0)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").uniform_(-1, 1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    print(json.dumps({"calibration": "plain copy", "read_bytes_per_launch": nbytes,
+                      "write_bytes_per_launch": nbytes, "launches": steps, "ms_per_launch": ms,
+                      "GB/s": 2 * nbytes / ms / 1e6}))
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    if a committed summary under profiles/ carries it."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("hbm_bytes_per_launch:"):
+            return float(line.split(":", 1)[1].split()[0])
+    return None
+
+
+def cpu_baseline(roots, parents, weights, k, n, chunk):
+    """The oracle as it stands, timed on the host: literal step-list execution
+    in NumPy float32 over the full headline workload (one pass)."""
+    import numpy as np
+
+    import synth_inputs as si
+    from oracle import execute as ox
+    from oracle import schedule as osch
+
+    steps = osch.make_steps(roots, parents, weights, osch.ALLREDUCE, n, chunk)
+    bufs = [si.payload(0, r, n, "uniform", "fp32") for r in range(k)]
+    t0 = time.perf_counter()
+    ox.run_steps(bufs, steps)
+    dt = time.perf_counter() - t0
+    return {"value": n * 4 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"full workload, one pass: {k} ranks x {n} fp32, {len(steps)} steps, "
+                      f"{dt:.2f} s; NumPy elementwise ops are single-threaded "
+                      f"(host has {os.cpu_count()} logical CPUs, "
+                      f"{len(os.sched_getaffinity(0))} usable)",
+            "seconds": dt}, bufs[0]
+
+
+def main():
+    args = parse()
+    if args.calibrate_copy:
+        calibrate_copy(args.steps)
+        return
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the k ranks are k HBM buffers on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1910_04940_amd as bl
+    import synth_inputs as si
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    top = si.hybrid_cube_mesh()
+    k, n = top.k, args.elems
+    chunk = args.chunk_bytes // 4
+    fusion = {"edge": bl.BLINK_FUSE_EDGE, "node": bl.BLINK_FUSE_NODE, "tree": bl.BLINK_FUSE_TREE}[args.fusion]
+    dtype = bl.BLINK_FP32 if args.dtype == "fp32" else bl.BLINK_INT32
+
+    trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
+    roots, parents, weights = trees.as_lists()
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    if args.unroll or args.wg_per_cu:
+        sched.set_launch(args.wg_per_cu, args.unroll)
+
+    # inputs: uniform[-1,1] (or full-range int32), generated on the host from the
+    # shared seeded recipe, resident in HBM before anything is timed
+    dist = "uniform" if args.dtype == "fp32" else "int"
+    pristine = [torch.from_numpy(si.payload(0, r, n, dist, args.dtype)).to(dev) for r in range(k)]
+    bufs = [p.clone() for p in pristine]
+    stream = torch.cuda.current_stream()
+
+    def restore():
+        for b, p in zip(bufs, pristine):
+            b.copy_(p)
+
+    def step():
+        bl.blink_allreduce(bufs, n, dtype, sched, stream.cuda_stream)
+
+    since_restore = 0
+    for _ in range(args.warmup):
+        if since_restore == MAX_STEPS_BETWEEN_RESTORES:
+            restore()
+            since_restore = 0
+        step()
+        since_restore += 1
+    restore()
+    since_restore = 0
+    restores = 0
+    torch.cuda.synchronize()
+
+    # per-launch kernel time with HIP events on the launch stream, and the whole bracket
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if since_restore == MAX_STEPS_BETWEEN_RESTORES:
+            restore()
+            restores += 1
+            since_restore = 0
+        evs[i][0].record(stream)
+        step()
+        evs[i][1].record(stream)
+        since_restore += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in evs]
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+
+    ms_per_step = wall * 1e3 / args.steps
+    value = n * 4 / (ms_per_step * 1e-3) / 1e9
+
+    per_elem = {"edge": 20 * (k - 1), "node": None, "tree": 8 * k}[args.fusion]
+    alg_bytes = sched.traffic_bytes          # == per_elem * n for edge and tree
+    if per_elem is not None:
+        assert alg_bytes == per_elem * n
+    achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    prof_name = f"blink_consume_allreduce_cube8_256MiB_{args.fusion}.txt"
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic_from_profiles(prof_name) if n == 1 << 26 else None,
+                "algorithmic_bytes_per_launch": alg_bytes,
+                "bytes_per_element": alg_bytes / n,
+                "accounting": {"edge": "per-edge: every tree edge is a transfer between two rank buffers, 20(k-1) B/elt",
+                               "node": "per-node: one pass per fan-in and per fan-out",
+                               "tree": "staged minimum: every rank buffer read once and written once, 8k B/elt"}[args.fusion],
+                "kernel": "blink_consume", "avg_kernel_ms": avg_kernel_ms,
+                "min_kernel_ms": min(kernel_ms)}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.dtype == "fp32" else "i32",
+        "data": "synthetic",
+        "config": {"workload": "AllReduce, 8 virtual ranks (HBM buffers on one GPU), unit-capacity hybrid "
+                               "cube-mesh, root 0, 4 packed unit trees, "
+                               f"{n} {args.dtype} per rank, {args.chunk_bytes} B chunks, uniform[-1,1] seed 0",
+                   "ranks": k, "elements_per_rank": n, "chunk_bytes": args.chunk_bytes,
+                   "trees": trees.count, "fusion": args.fusion, "stages": sched.num_stages,
+                   "steps_in_schedule": sched.num_steps, "restores_in_timed_region": restores},
+        "roofline": roofline,
+    }
+
+    if args.check or not args.no_cpu_baseline:
+        # leave the device with exactly one AllReduce applied to the pristine inputs
+        restore()
+        step()
+        torch.cuda.synchronize()
+    if not args.no_cpu_baseline and args.dtype == "fp32":
+        base, want = cpu_baseline(roots, parents, weights, k, n, chunk)
+        out["cpu_baseline"] = base
+        got = bufs[k - 1].cpu().numpy()
+        same = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
+        out["config"]["matches_oracle_bitwise"] = same
+        if not same:
+            print("bench.py: GPU result differs from the oracle", file=sys.stderr)
+            print(json.dumps(out))
+            sys.exit(1)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
