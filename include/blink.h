@@ -54,7 +54,7 @@ typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
 typedef enum { BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1 } blink_op_t;
 typedef enum { BLINK_STEP_REDUCE = 0, BLINK_STEP_COPY = 1 } blink_step_kind_t;
 
-/* How many tree-edge transfers one workgroup carries a tile through before the
+/* How many tree-edge transfers one wavefront carries a tile through before the
  * data returns to HBM.  The result is bit-identical for all three.
  *   EDGE  one transfer per step, as the paper issues them: a REDUCE reads both
  *         rank buffers and writes the parent's, a COPY reads the parent's and
@@ -166,10 +166,12 @@ blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_d
 blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                                blink_schedule_t* s, void* stream);
 
-/* Launch shape override for tuning: workgroups per compute unit (0 = as many as
- * fit) and 128-bit accesses per thread per buffer and tile (0 = automatic; 1, 2
- * or 4).  Applies to later calls on this schedule. */
-blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int unroll);
+/* Launch shape override for tuning: waves per compute unit (0 = automatic) and
+ * elements per tile, the unit of work a wave draws at a time (0 = automatic;
+ * else a power of two in [256, 65536]).  Changing the tile size waits for the
+ * device and restarts the schedule's progress counters.  Applies to later
+ * calls on this schedule. */
+blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
 
 const char* blink_strerror(blink_status_t st);
 

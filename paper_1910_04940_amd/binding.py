@@ -236,8 +236,8 @@ class Schedule:
                "blink_schedule_get_bounds")
         return [int(x) for x in out]
 
-    def set_launch(self, wg_per_cu: int = 0, unroll: int = 0) -> None:
-        _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, unroll), "blink_schedule_set_launch")
+    def set_launch(self, wg_per_cu: int = 0, tile_elems: int = 0) -> None:
+        _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, tile_elems), "blink_schedule_set_launch")
 
 
 def blink_make_schedule(trees: Trees, op: int, n_elems: int, chunk_elems: int,

@@ -146,13 +146,14 @@ blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_d
     BLINK_GUARD_END
 }
 
-blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int unroll) {
-    if (!s || wg_per_cu < 0 || !(unroll == 0 || unroll == 1 || unroll == 2 || unroll == 4))
-        return BLINK_EINVAL;
+blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems) {
+    const bool tile_ok = tile_elems == 0 || (tile_elems >= 256 && tile_elems <= 65536 &&
+                                             (tile_elems & (tile_elems - 1)) == 0);
+    if (!s || wg_per_cu < 0 || !tile_ok) return BLINK_EINVAL;
     s->wg_per_cu = wg_per_cu;
-    if (unroll != s->unroll) {
-        s->unroll = unroll;
-        return blink::reset_progress(s);
+    if (static_cast<unsigned>(tile_elems) != s->tile_override) {
+        s->tile_override = static_cast<unsigned>(tile_elems);
+        return blink::reset_progress(s);  // counters were counted in tiles of the old size
     }
     return BLINK_OK;
 }

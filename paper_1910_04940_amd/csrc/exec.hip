@@ -8,8 +8,12 @@
 // to wait for has already been drawn by a wave that is running: waiting can
 // never deadlock, whatever the grid size.
 //
-// A tile is kSub sub-tiles; a sub-tile of a stage is processed in three phases
-// by the 64 lanes, each owning U 128-bit columns:
+// A tile (256..65536 elements, chosen per schedule) is cut into sub-tiles; a
+// sub-tile of a stage is processed in three phases by the 64 lanes, each owning
+// U 128-bit columns, where U is as large as the stage allows under a budget of
+// 16 columns in registers (a stage that reads 8 ranks gets U = 2, a plain copy
+// U = 16), so that every wave keeps about 16 KiB of loads in flight whatever
+// the stage looks like:
 //   1. load the sub-tile from every rank the stage reads; all loads are issued
 //      before the first is consumed, then parked in per-lane LDS slots;
 //   2. run the stage's micro-program (acc = slot / acc += slot / slot = acc)
@@ -20,8 +24,9 @@
 //
 // Chunk-granular hand-over (the paper's per-chunk event): a stage instance has
 // a 64-bit counter of finished tiles.  Counters are never reset; call number e
-// on a schedule waits for e * tiles.  A consumer polls with agent-scope atomic
-// loads, then acquires; a producer releases at agent scope and increments.
+// on a schedule waits for e * tiles.  Data handed from stage to stage travels
+// with system-scope cache policy (see blink_consume), the counters with
+// agent-scope atomics.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -34,11 +39,18 @@
 
 namespace blink {
 
-constexpr int kLanes = 64;   // one wavefront per workgroup
-constexpr int kSub = 4;      // sub-tiles per ticket
-// 128-bit columns a lane may hold in registers at once (ranks read x unroll):
-// keeps the load phase inside the register file.
-constexpr int kMaxColumns = 16;
+constexpr int kLanes = 64;        // one wavefront per workgroup
+constexpr int kMaxColumns = 16;   // 128-bit columns a lane holds in registers at once (ranks read x U)
+constexpr unsigned kMinTile = kLanes * 4;   // elements: one column per lane
+constexpr unsigned kMaxTile = 65536;        // elements
+// One ticket counter serves the whole chip; it sustains roughly 80 draws per
+// microsecond.  A ticket should therefore move about this many bytes, so that
+// drawing tickets stays an order of magnitude away from being the bottleneck.
+constexpr unsigned kTicketBytes = 128 * 1024;
+// Progress counters sit 256 bytes apart: the few counters that are hot at any
+// moment then live in different cache lines and memory channels, so thousands
+// of polling waves do not pile up on one of them.
+constexpr int kCounterStride = 32;  // in 8-byte words
 
 struct KParams {
     void* buf[BLINK_MAX_RANKS];
@@ -50,22 +62,42 @@ struct KParams {
     unsigned long long n_items;
     unsigned long long epoch;
     unsigned tiles_per_chunk;
+    unsigned tile_elems;
+    unsigned group;  // consecutive instances whose tiles are handed out in turn (1 = instance by instance)
 };
 
-// Address spaces: rank buffers are plain global memory; the kernel arguments
-// and the schedule tables are never written by the kernel, so they are read
-// through the constant address space, which lets wave-uniform reads use the
-// scalar unit.
-#define BLINK_GLOBAL __attribute__((address_space(1)))
+// Address spaces: the kernel arguments and the schedule tables are never
+// written by the kernel, so they are read through the constant address space,
+// which lets wave-uniform reads use the scalar unit.
 #define BLINK_CONST __attribute__((address_space(4)))
 using ConstParams = const BLINK_CONST KParams*;
 using ConstTmpl = const BLINK_CONST StageTmpl*;
 using ConstInst = const BLINK_CONST StageInst*;
 
-typedef float F4 __attribute__((ext_vector_type(4)));     // one 128-bit access of fp32
-typedef unsigned U4 __attribute__((ext_vector_type(4)));  // int32 payloads add as unsigned: wrap-around, no UB
-template <typename V>
-__device__ __forceinline__ V vadd(V a, V b) {
+typedef float F4 __attribute__((ext_vector_type(4)));
+typedef unsigned U4 __attribute__((ext_vector_type(4)));  // one 128-bit access, as raw bits
+
+// Element-wise add on raw bits.  fp32: one IEEE add per element (round to
+// nearest even, subnormals kept).  int32: unsigned add, i.e. wrap-around
+// modulo 2^32 without signed-overflow UB.
+template <typename T>
+__device__ __forceinline__ U4 vadd(U4 a, U4 b);
+template <>
+__device__ __forceinline__ U4 vadd<float>(U4 a, U4 b) {
+    return __builtin_bit_cast(U4, __builtin_bit_cast(F4, a) + __builtin_bit_cast(F4, b));
+}
+template <>
+__device__ __forceinline__ U4 vadd<unsigned>(U4 a, U4 b) {
+    return a + b;
+}
+template <typename T>
+__device__ __forceinline__ unsigned sadd(unsigned a, unsigned b);
+template <>
+__device__ __forceinline__ unsigned sadd<float>(unsigned a, unsigned b) {
+    return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b));
+}
+template <>
+__device__ __forceinline__ unsigned sadd<unsigned>(unsigned a, unsigned b) {
     return a + b;
 }
 
@@ -77,94 +109,148 @@ __device__ __forceinline__ unsigned tmpl_byte(ConstTmpl st, unsigned byte_index)
 }
 #define BLINK_TMPL(st, field, i) tmpl_byte(st, static_cast<unsigned>(offsetof(StageTmpl, field)) + (i))
 
-template <typename V>
-__device__ __forceinline__ BLINK_GLOBAL V* rank_ptr(ConstParams p, unsigned rank, unsigned long long byte_off) {
-    return reinterpret_cast<BLINK_GLOBAL V*>(reinterpret_cast<unsigned long long>(p->buf[rank]) + byte_off);
+// Rank buffers are accessed through buffer descriptors that cover exactly the
+// bytes still to be processed: lanes past the end read zeros and their stores
+// are dropped by the hardware range check, so ragged ends need no branches.
+// The cache-policy bits of each access are chosen per kernel flavour (below).
+constexpr int kRawDword3 = 0x00020000;  // raw 32-bit data format, no swizzle (gfx9 family)
+constexpr int kPolicyStream = 2;        // nt: streamed once, do not keep in cache
+constexpr int kPolicySystem = 17;       // sc0 sc1: bypass / write through every cache level
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rank_window(ConstParams p, unsigned rank,
+                                                              unsigned long long byte_off, unsigned bytes) {
+    char* base = reinterpret_cast<char*>(reinterpret_cast<unsigned long long>(p->buf[rank]) + byte_off);
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, static_cast<int>(bytes), kRawDword3);
 }
 
-// Phase 1, full tile, NL ranks: issue every load, then park the values in LDS.
-template <typename V, int NL, int U>
-__device__ __forceinline__ void load_slots_full(V* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                                unsigned long long byte_off, int tid) {
-    V r[NL][U];
+// Phases 1-3 over `bytes` bytes (a multiple of 16) at byte_off for a stage that
+// reads N ranks, U columns per lane and sub-tile.
+template <typename T, int N, int U, int LD, int ST>
+__device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+                                        unsigned long long byte_off, unsigned bytes, int lane) {
+    constexpr unsigned kSubBytes = kLanes * U * 16;
+    const int n_op = BLINK_TMPL(st, n_op, 0);
+    const int n_store = BLINK_TMPL(st, n_store, 0);
+    for (unsigned b = 0; b < bytes; b += kSubBytes) {
+        const unsigned left = bytes - b;
+        // phase 1: issue every load, then park the values in LDS
+        U4 r[N][U];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-        const BLINK_GLOBAL V* src = rank_ptr<V>(p, BLINK_TMPL(st, load_rank, i), byte_off);
+        for (int i = 0; i < N; ++i) {
+            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off + b, left);
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[i][u] = src[u * kLanes + tid];
-    }
-#pragma unroll
-    for (int i = 0; i < NL; ++i)
-#pragma unroll
-        for (int u = 0; u < U; ++u) slots[(i * U + u) * kLanes + tid] = r[i][u];
-}
-
-// Phases 1-3 for `nvec` elements of type V starting at byte_off.  FULL: the
-// tile has all kLanes*U elements (the common case, no per-lane guards).
-template <typename V, int U, bool FULL>
-__device__ __forceinline__ void run_tile(V* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                         unsigned long long byte_off, unsigned nvec, int tid) {
-    const int n_load = BLINK_TMPL(st, n_load, 0);
-    if constexpr (FULL) {
-        switch (n_load) {
-#define BLINK_CASE(N)                                                              \
-    case N:                                                                        \
-        if constexpr (N * U <= kMaxColumns)                                        \
-            load_slots_full<V, N, U>(slots, p, st, byte_off, tid);                 \
-        break;
-            BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
-            BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
-            BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
-#undef BLINK_CASE
-            default: break;
+            for (int u = 0; u < U; ++u)
+                r[i][u] = __builtin_amdgcn_raw_buffer_load_b128(win, (u * kLanes + lane) * 16, 0, LD);
         }
-    } else {
-        for (int i = 0; i < n_load; ++i) {
-            const BLINK_GLOBAL V* src = rank_ptr<V>(p, BLINK_TMPL(st, load_rank, i), byte_off);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const unsigned idx = u * kLanes + tid;
-                if (idx < nvec) slots[(i * U + u) * kLanes + tid] = src[idx];
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int u = 0; u < U; ++u) slots[(i * U + u) * kLanes + lane] = r[i][u];
+        // phase 2: the stage's micro-program
+        U4 acc[U];
+        for (int o = 0; o < n_op; ++o) {
+            const unsigned code = BLINK_TMPL(st, op, o);
+            U4* sl = slots + (code & 63u) * (U * kLanes) + lane;
+            const unsigned kind = code >> 6;
+            if (kind == OP_LD) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
+            } else if (kind == OP_ADD) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] = vadd<T>(acc[u], sl[u * kLanes]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
             }
         }
+        // phase 3: stores
+        for (int j = 0; j < n_store; ++j) {
+            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off + b, left);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                __builtin_amdgcn_raw_buffer_store_b128(acc[u], win, (u * kLanes + lane) * 16, 0, ST);
+        }
     }
-    V acc[U];
+}
+
+// Pick U for a stage that reads N ranks: the largest power of two with
+// N * U <= kMaxColumns that does not exceed the tile (cols = tile columns per lane).
+template <typename T, int N, int LD, int ST>
+__device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+                                          unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
+    constexpr int kBudget = N <= 1 ? 16 : (N <= 2 ? 8 : (N <= 4 ? 4 : (N <= 8 ? 2 : 1)));
+    if constexpr (kBudget >= 16)
+        if (cols >= 16) return run_vec<T, N, 16, LD, ST>(slots, p, st, byte_off, bytes, lane);
+    if constexpr (kBudget >= 8)
+        if (cols >= 8) return run_vec<T, N, 8, LD, ST>(slots, p, st, byte_off, bytes, lane);
+    if constexpr (kBudget >= 4)
+        if (cols >= 4) return run_vec<T, N, 4, LD, ST>(slots, p, st, byte_off, bytes, lane);
+    if constexpr (kBudget >= 2)
+        if (cols >= 2) return run_vec<T, N, 2, LD, ST>(slots, p, st, byte_off, bytes, lane);
+    run_vec<T, N, 1, LD, ST>(slots, p, st, byte_off, bytes, lane);
+}
+
+template <typename T, int LD, int ST>
+__device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+                                            unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
+    switch (BLINK_TMPL(st, n_load, 0)) {
+#define BLINK_CASE(N) case N: run_vec_n<T, N, LD, ST>(slots, p, st, byte_off, bytes, cols, lane); break;
+        BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
+        BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
+        BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
+#undef BLINK_CASE
+        default: break;
+    }
+}
+
+// The same for up to kLanes single 4-byte elements: the ragged end of a payload
+// whose length is not a multiple of 4 elements, and chunks that do not start on
+// a 16-byte boundary.  Slow path; one element per lane.
+template <typename T, int LD, int ST>
+__device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstParams p, ConstTmpl st,
+                                           unsigned long long byte_off, unsigned bytes, int lane) {
+    const int n_load = BLINK_TMPL(st, n_load, 0);
+    for (int i = 0; i < n_load; ++i) {
+        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off, bytes);
+        slots[i * kLanes + lane] = __builtin_amdgcn_raw_buffer_load_b32(win, lane * 4, 0, LD);
+    }
+    unsigned acc = 0;
     const int n_op = BLINK_TMPL(st, n_op, 0);
     for (int o = 0; o < n_op; ++o) {
         const unsigned code = BLINK_TMPL(st, op, o);
-        V* sl = slots + (code & 63u) * (U * kLanes) + tid;
+        unsigned* sl = slots + (code & 63u) * kLanes + lane;
         const unsigned kind = code >> 6;
-        if (kind == OP_LD) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
-        } else if (kind == OP_ADD) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = vadd(acc[u], sl[u * kLanes]);
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
-        }
+        if (kind == OP_LD)
+            acc = *sl;
+        else if (kind == OP_ADD)
+            acc = sadd<T>(acc, *sl);
+        else
+            *sl = acc;
     }
     const int n_store = BLINK_TMPL(st, n_store, 0);
     for (int j = 0; j < n_store; ++j) {
-        BLINK_GLOBAL V* dst = rank_ptr<V>(p, BLINK_TMPL(st, store_rank, j), byte_off);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned idx = u * kLanes + tid;
-            if (FULL || idx < nvec) dst[idx] = acc[u];
-        }
+        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off, bytes);
+        __builtin_amdgcn_raw_buffer_store_b32(acc, win, lane * 4, 0, ST);
     }
 }
 
-// T: element type (float, or unsigned for wrap-around int32); V4: its 128-bit vector.
+// T: element type (float, or unsigned for wrap-around int32).  COHERENT selects
+// how data is exchanged between stages:
+//   false  the schedule has no stage that waits for another (TREE fusion):
+//          streaming (nt) accesses, no fences;
+//   true   stages hand chunks over to each other, possibly across XCDs whose L2
+//          caches are not coherent with one another: all rank-buffer accesses
+//          use system-scope cache policy (loads bypass, stores write through),
+//          so the hand-over needs no L2 write-back or invalidate, only "my
+//          stores have completed" before the counter is bumped.
 // The by-value argument is only there to size the kernel-argument segment; it is
 // read through the constant address space (see ConstParams).
-template <typename T, typename V4, int U>
+template <typename T, bool COHERENT>
 __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
+    __shared__ U4 slots[kMaxColumns * kLanes];  // 16 KiB: 16 columns per lane
+    constexpr int LD = COHERENT ? kPolicySystem : kPolicyStream;
+    constexpr int ST = COHERENT ? kPolicySystem : kPolicyStream;
     const int lane = threadIdx.x;
-    constexpr unsigned kSubTile = kLanes * 4 * U;   // elements per sub-tile
-    constexpr unsigned kTile = kSubTile * kSub;     // elements per ticket
     ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
     unsigned long long* const ticket = p->ticket;
     unsigned long long* const done = p->done;
@@ -172,7 +258,10 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     ConstInst const inst = reinterpret_cast<ConstInst>(reinterpret_cast<unsigned long long>(p->inst));
     const unsigned long long n_items = p->n_items, ticket_base = p->ticket_base, epoch = p->epoch;
     const unsigned tiles_per_chunk = p->tiles_per_chunk;
-    V4* const slots = reinterpret_cast<V4*>(lds_raw);
+    const unsigned tile_elems = p->tile_elems;
+    const unsigned cols = min(tile_elems / kMinTile, static_cast<unsigned>(kMaxColumns));
+    const unsigned group = p->group;
+    const unsigned n_inst = static_cast<unsigned>(n_items / tiles_per_chunk);
 
     // The loop has exactly one lane-dependent region, at its head, and one back
     // edge: the compiler must never get the chance to let some lanes run ahead
@@ -183,7 +272,8 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
         unsigned long long raw = 0;
         if (lane == 0) {
             if (pending >= 0)
-                __hip_atomic_fetch_add(done + pending, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(done + pending * kCounterStride, 1ull, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
             raw = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ticket_base;
         }
         pending = -1;
@@ -191,45 +281,59 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
         const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw >> 32));
         const unsigned long long t = (static_cast<unsigned long long>(hi) << 32) | lo;
         if (t >= n_items) break;
-        const unsigned ii = static_cast<unsigned>(t / tiles_per_chunk);
-        const unsigned tile = static_cast<unsigned>(t % tiles_per_chunk);
+        // ticket -> (instance, tile).  Within a group of `group` consecutive
+        // instances (the trees' turns at one chunk position) tickets walk tile
+        // by tile across the instances, so neighbouring waves work on all trees
+        // at once (section 4.2.2); group == 1 keeps an instance's tiles together.
+        const unsigned long long per_group = static_cast<unsigned long long>(group) * tiles_per_chunk;
+        const unsigned first = static_cast<unsigned>(t / per_group) * group;
+        const unsigned members = min(group, n_inst - first);
+        const unsigned within = static_cast<unsigned>(t - static_cast<unsigned long long>(first) * tiles_per_chunk);
+        const unsigned ii = first + within % members;
+        const unsigned tile = within / members;
         ConstInst in = inst + ii;
         const unsigned len = in->len;
-        const unsigned long long tile_off = static_cast<unsigned long long>(tile) * kTile;
+        const unsigned long long tile_off = static_cast<unsigned long long>(tile) * tile_elems;
         if (tile_off < len) {  // a short last chunk has fewer tiles than tickets
-            const unsigned tlen = min(kTile, static_cast<unsigned>(len - tile_off));
+            const unsigned tlen = min(tile_elems, static_cast<unsigned>(len - tile_off));
             ConstTmpl st = tmpl + in->tmpl;
 
             const int n_dep = in->n_dep;
             if (n_dep) {
                 if (lane < n_dep) {
-                    const unsigned long long want = epoch * ((len + kTile - 1) / kTile);
-                    const unsigned long long* f = done + in->dep[lane];
-                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want)
-                        __builtin_amdgcn_s_sleep(2);
+                    const unsigned long long want = epoch * ((len + tile_elems - 1) / tile_elems);
+                    const unsigned long long* f = done + static_cast<long long>(in->dep[lane]) * kCounterStride;
+                    // poll, backing off up to ~2 us between looks so that waiting
+                    // waves leave the memory system to the working ones
+                    int naps = 1;
+                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+                        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
+                        if (naps < 8) naps *= 2;
+                    }
                 }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                // orders the polls before the data loads; the loads themselves bypass the caches
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             }
 
             const unsigned long long e0 = in->off + tile_off;  // first element of the tile
             if ((e0 & 3ull) == 0) {
-                const unsigned nvec = tlen >> 2;
-                unsigned v = 0;
-                for (; v + kLanes * U <= nvec; v += kLanes * U)
-                    run_tile<V4, U, true>(slots, p, st, (e0 + 4ull * v) * 4ull, kLanes * U, lane);
-                if (v < nvec) run_tile<V4, U, false>(slots, p, st, (e0 + 4ull * v) * 4ull, nvec - v, lane);
+                const unsigned vec_bytes = (tlen >> 2) * 16u;
+                if (vec_bytes) run_vec_any<T, LD, ST>(slots, p, st, e0 * 4ull, vec_bytes, cols, lane);
                 const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
                 if (rem)
-                    run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + (nvec << 2)) * 4ull, rem, lane);
+                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + vec_bytes,
+                                          rem * 4u, lane);
             } else {
                 // chunk size not a multiple of 4 elements: element-wise, slow but correct
-                for (unsigned done_e = 0; done_e < tlen; done_e += kLanes)
-                    run_tile<T, 1, false>(reinterpret_cast<T*>(lds_raw), p, st, (e0 + done_e) * 4ull,
-                                          min(static_cast<unsigned>(kLanes), tlen - done_e), lane);
+                for (unsigned b = 0; b < tlen * 4u; b += kLanes * 4u)
+                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + b,
+                                          min(static_cast<unsigned>(kLanes) * 4u, tlen * 4u - b), lane);
             }
 
             if (BLINK_TMPL(st, signals, 0)) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                // every store of this wave has reached memory before the counter moves
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_s_waitcnt(0);
                 pending = ii;
             }
         }
@@ -250,15 +354,14 @@ namespace {
 
 using KernelFn = void (*)(const KParams);
 
-KernelFn pick_kernel(blink_dtype_t dtype, int unroll) {
-    if (dtype == BLINK_FP32) {
-        if (unroll == 1) return blink_consume<float, F4, 1>;
-        if (unroll == 2) return blink_consume<float, F4, 2>;
-        return blink_consume<float, F4, 4>;
-    }
-    if (unroll == 1) return blink_consume<unsigned, U4, 1>;
-    if (unroll == 2) return blink_consume<unsigned, U4, 2>;
-    return blink_consume<unsigned, U4, 4>;
+KernelFn pick_kernel(blink_dtype_t dtype, bool coherent) {
+    if (dtype == BLINK_FP32) return coherent ? blink_consume<float, true> : blink_consume<float, false>;
+    return coherent ? blink_consume<unsigned, true> : blink_consume<unsigned, false>;
+}
+
+// word 0: the ticket counter; then one counter per stage instance, kCounterStride words apart
+size_t counter_bytes(const Schedule& s) {
+    return (s.inst.size() + 1) * static_cast<size_t>(kCounterStride) * sizeof(unsigned long long);
 }
 
 blink_status_t upload(blink_schedule* h) {
@@ -269,10 +372,10 @@ blink_status_t upload(blink_schedule* h) {
     const Schedule& s = h->s;
     BLINK_HIP(hipMalloc(&h->d_tmpl, s.tmpl.size() * sizeof(StageTmpl)));
     BLINK_HIP(hipMalloc(&h->d_inst, s.inst.size() * sizeof(StageInst)));
-    BLINK_HIP(hipMalloc(&h->d_counters, (s.inst.size() + 1) * sizeof(unsigned long long)));
+    BLINK_HIP(hipMalloc(&h->d_counters, counter_bytes(s)));
     BLINK_HIP(hipMemcpy(h->d_tmpl, s.tmpl.data(), s.tmpl.size() * sizeof(StageTmpl), hipMemcpyHostToDevice));
     BLINK_HIP(hipMemcpy(h->d_inst, s.inst.data(), s.inst.size() * sizeof(StageInst), hipMemcpyHostToDevice));
-    BLINK_HIP(hipMemset(h->d_counters, 0, (s.inst.size() + 1) * sizeof(unsigned long long)));
+    BLINK_HIP(hipMemset(h->d_counters, 0, counter_bytes(s)));
     BLINK_HIP(hipDeviceSynchronize());
     hipDeviceProp_t prop;
     BLINK_HIP(hipGetDeviceProperties(&prop, dev));
@@ -288,10 +391,10 @@ blink_status_t upload(blink_schedule* h) {
 blink_status_t reset_progress(blink_schedule* h) {
     h->epoch = 0;
     h->ticket_base = 0;
-    for (auto& row : h->occupancy) for (int& x : row) x = 0;
+    h->tile_elems = 0;
     if (h->device < 0) return BLINK_OK;
     BLINK_HIP(hipDeviceSynchronize());
-    BLINK_HIP(hipMemset(h->d_counters, 0, (h->s.inst.size() + 1) * sizeof(unsigned long long)));
+    BLINK_HIP(hipMemset(h->d_counters, 0, counter_bytes(h->s)));
     BLINK_HIP(hipDeviceSynchronize());
     return BLINK_OK;
 }
@@ -321,46 +424,64 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     if (n == 0 || s.inst.empty()) return BLINK_OK;
     if (blink_status_t st = upload(h)) return st;
 
-    int unroll = h->unroll;
-    if (unroll == 0) unroll = s.max_slots <= 4 ? 4 : (s.max_slots <= 8 ? 2 : 1);
-    const unsigned tile = kLanes * 4 * unroll * kSub;
-    uint32_t longest = 0;
-    for (const StageInst& in : s.inst) longest = std::max(longest, in.len);
-    const unsigned tiles_per_chunk = (longest + tile - 1) / tile;
-    const unsigned long long n_items = static_cast<unsigned long long>(s.inst.size()) * tiles_per_chunk;
-    if (static_cast<int>(s.max_slots) * unroll > kMaxColumns) return BLINK_EINVAL;
-    const size_t lds = static_cast<size_t>(s.max_slots) * unroll * kLanes * 16;
-
-    KernelFn fn = pick_kernel(dtype, unroll);
-    int& cached = h->occupancy[dtype == BLINK_FP32][unroll == 1 ? 0 : (unroll == 2 ? 1 : 2)];
+    KernelFn fn = pick_kernel(dtype, s.has_deps);
+    int& cached = h->occupancy[dtype == BLINK_FP32];
     if (cached == 0) {
-        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, lds));
+        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, 0));
         if (cached < 1) {
             cached = 0;
             return BLINK_EHIP;
         }
     }
-    int per_cu = cached;
-    if (h->wg_per_cu > 0) per_cu = std::min(per_cu, h->wg_per_cu);
-    const unsigned long long grid =
-        std::min<unsigned long long>(static_cast<unsigned long long>(per_cu) * h->n_cu, n_items);
+    // A few waves per CU, each with ~16 KiB of loads in flight, saturate HBM;
+    // more waves only add ticket and polling traffic and disturb DRAM page
+    // locality (measured: 3 is best for pure streaming, 4 when stages wait).
+    int per_cu = std::min(cached, s.has_deps ? 4 : 3);
+    if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
+    const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
+
+    // Tile size: the largest that still leaves every wave several tickets (small
+    // payloads get small tiles so that the whole chip takes part).  It stays
+    // fixed for the life of the schedule unless overridden, because the progress
+    // counters count tiles.
+    if (h->tile_elems == 0) {
+        if (h->tile_override) {
+            h->tile_elems = h->tile_override;
+        } else {
+            uint64_t work = 0;  // elements x stages
+            for (const StageInst& in : s.inst) work += in.len;
+            const uint64_t bytes_per_elem = std::max<uint64_t>(1, s.traffic_bytes / std::max<uint64_t>(1, work));
+            unsigned tile = kMinTile;
+            while (tile < kMaxTile && static_cast<uint64_t>(tile) * bytes_per_elem < kTicketBytes) tile *= 2;
+            while (tile > kMinTile && work / tile < 6 * max_grid) tile /= 2;
+            h->tile_elems = tile;
+        }
+    }
+    const unsigned tile = h->tile_elems;
+    uint32_t longest = 0;
+    for (const StageInst& in : s.inst) longest = std::max(longest, in.len);
+    const unsigned tiles_per_chunk = (longest + tile - 1) / tile;
+    const unsigned long long n_items = static_cast<unsigned long long>(s.inst.size()) * tiles_per_chunk;
+    const unsigned long long grid = std::min<unsigned long long>(max_grid, n_items);
 
     KParams p{};
     for (int i = 0; i < k; ++i) p.buf[i] = bufs[i];
     p.tmpl = static_cast<const StageTmpl*>(h->d_tmpl);
     p.inst = static_cast<const StageInst*>(h->d_inst);
-    p.done = static_cast<unsigned long long*>(h->d_counters) + 1;
+    p.done = static_cast<unsigned long long*>(h->d_counters) + kCounterStride;
     p.ticket = static_cast<unsigned long long*>(h->d_counters);
     p.ticket_base = h->ticket_base;
     p.n_items = n_items;
     p.epoch = ++h->epoch;
     p.tiles_per_chunk = tiles_per_chunk;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), lds,
+    p.tile_elems = tile;
+    // Without dependencies the order of tiles is free: interleave the trees tile by tile.
+    p.group = s.has_deps ? 1u : static_cast<unsigned>(s.n_trees);
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), 0,
                        static_cast<hipStream_t>(stream), p);
     BLINK_HIP(hipGetLastError());
-    h->ticket_base += n_items + grid;  // every workgroup draws exactly one ticket past the end
+    h->ticket_base += n_items + grid;  // every wave draws exactly one ticket past the end
     h->last_grid = static_cast<unsigned>(grid);
-    h->last_unroll = unroll;
     return BLINK_OK;
 }
 

@@ -380,7 +380,11 @@ blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint
     }
     out.max_slots = 1;
     out.traffic_bytes = 0;
-    for (const StageTmpl& st : out.tmpl) out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
+    out.has_deps = false;
+    for (const StageTmpl& st : out.tmpl) {
+        out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
+        out.has_deps = out.has_deps || st.n_dep > 0;
+    }
     for (const StageInst& in : out.inst) {
         const StageTmpl& st = out.tmpl[in.tmpl];
         out.traffic_bytes += static_cast<uint64_t>(in.len) * 4u * (st.n_load + st.n_store);

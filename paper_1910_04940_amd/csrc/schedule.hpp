@@ -52,6 +52,7 @@ struct Schedule {
     std::vector<StageTmpl> tmpl;
     std::vector<StageInst> inst;         // execution (ticket) order; dependencies point backwards
     uint32_t max_slots = 1;              // largest n_load
+    bool has_deps = false;               // some stage waits for another
     uint64_t traffic_bytes = 0;
 };
 

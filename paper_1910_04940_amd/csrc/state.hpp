@@ -14,10 +14,11 @@ struct blink_schedule {
     uint64_t epoch = 0;           // calls made so far; counters hold epoch * tiles
     uint64_t ticket_base = 0;     // value of the ticket counter when the next call starts
     int n_cu = 0;
-    int wg_per_cu = 0, unroll = 0;  // launch overrides (0 = automatic)
-    int occupancy[2][3] = {{0, 0, 0}, {0, 0, 0}};  // cached per dtype and unroll
+    int wg_per_cu = 0;            // launch override (0 = automatic)
+    unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
+    unsigned tile_elems = 0;      // elements per tile in use (0 = not chosen yet)
+    int occupancy[2] = {0, 0};    // waves per CU, cached per dtype
     unsigned last_grid = 0;
-    int last_unroll = 0;
 };
 
 namespace blink {

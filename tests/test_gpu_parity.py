@@ -127,11 +127,9 @@ def test_sixteen_rank_switch_one_hop_trees(dev, fusion):
 
 
 @pytest.mark.parametrize("fusion", FUSIONS)
-@pytest.mark.parametrize("launch", [(1, 1), (1, 2), (0, 1), (2, 0)])
+@pytest.mark.parametrize("launch", [(1, 256), (1, 4096), (0, 512), (2, 0), (16, 1024), (0, 65536), (3, 16384)])
 def test_launch_shapes_and_repeated_calls_on_one_schedule(dev, fusion, launch):
     top = si.hybrid_cube_mesh()
-    if launch[1] == 2 and fusion == bl.BLINK_FUSE_TREE:
-        pass  # 8 ranks x unroll 2 = 16 columns: allowed
     run_allreduce_case(dev, top, 0, n=200_000, chunk=16_384, dtype="int32", fusion=fusion,
                        seed=21, launch=launch, calls=3)
     run_allreduce_case(dev, top, 0, n=200_000, chunk=16_384, dtype="fp32", fusion=fusion,
@@ -252,13 +250,9 @@ def test_call_errors(dev):
     assert status(bl.blink_allreduce, ovl, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EINVAL
     null = [0] + [b.data_ptr() for b in bufs[1:]]
     assert status(bl.blink_allreduce, null, n, bl.BLINK_FP32, sched, stream()) == bl.BLINK_EINVAL
-    assert status(sched.set_launch, 0, 3) == bl.BLINK_EINVAL
-    # 16 ranks read at once leave room for one 128-bit column per thread only
-    t16 = pack(si.complete_graph(16), bl.BLINK_ROOT_ANY)
-    s16 = bl.blink_make_schedule(t16, bl.BLINK_OP_ALLREDUCE, 1 << 16, 4096, bl.BLINK_FUSE_TREE)
-    s16.set_launch(0, 2)
-    b16 = [torch.zeros(1 << 16, device=dev) for _ in range(16)]
-    assert status(bl.blink_allreduce, b16, 1 << 16, bl.BLINK_FP32, s16, stream()) == bl.BLINK_EINVAL
+    for bad_tile in (3, 128, 131072, 768):
+        assert status(sched.set_launch, 0, bad_tile) == bl.BLINK_EINVAL
+    assert status(sched.set_launch, -1, 0) == bl.BLINK_EINVAL
     # the schedule still works after all those refusals
     bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
     torch.cuda.synchronize()
