@@ -187,3 +187,56 @@ def bucket_sizes(total_elems: int = 138_000_000, n_buckets: int = 16, seed: int 
     e[int(np.argmax(e))] += total_elems - int(e.sum())
     assert int(e.sum()) == total_elems and (e > 0).all()
     return [int(x) for x in e]
+
+
+# --------------------------------------------------------------------------
+# counter-based payloads: the same values from NumPy (any slice, on the host)
+# and from torch (whole buffers, generated where they live)
+# --------------------------------------------------------------------------
+_M31 = (1 << 31) - 1
+
+
+def _mix_numpy(seed: int, rank: int, idx: np.ndarray) -> np.ndarray:
+    """31-bit hash of (seed, rank, element index); int64 arithmetic that never
+    overflows (every product stays below 2^62), so NumPy and torch agree."""
+    x = (idx.astype(np.int64) ^ np.int64((seed * 7919 + rank * 104729 + 12345) & _M31)) & _M31
+    for mul, shift in ((1103515245, 13), (214013, 11), (69069, 15)):
+        x = (x * np.int64(mul) + np.int64(12345)) & _M31
+        x = x ^ (x >> shift)
+    hi = (idx.astype(np.int64) >> 31) & _M31          # indices beyond 2^31 still differ
+    x = ((x ^ hi) * np.int64(48271) + np.int64(11)) & _M31
+    return x ^ (x >> 16)
+
+
+def hash_payload(seed: int, rank: int, start: int, n: int, dtype: str) -> np.ndarray:
+    """Elements [start, start+n): fp32 uniform on the grid k*2^-23 - 1 in [-1, 1),
+    or int32 (31-bit hash shifted into the sign bit so that sums wrap)."""
+    h = _mix_numpy(seed, rank, np.arange(start, start + n, dtype=np.int64))
+    if dtype == "fp32":
+        return ((h >> 7).astype(np.float32) * np.float32(2.0 ** -23) - np.float32(1.0)).astype(np.float32)
+    if dtype == "int32":
+        return ((h << 1) & 0xFFFFFFFF).astype(np.uint32).view(np.int32)
+    raise ValueError(dtype)
+
+
+def hash_payload_torch(seed: int, rank: int, n: int, dtype: str, device, block: int = 1 << 24):
+    """The same values as hash_payload(seed, rank, 0, n, dtype), generated by
+    torch element-wise integer ops on `device` in blocks."""
+    import torch
+    out = torch.empty(n, dtype=torch.float32 if dtype == "fp32" else torch.int32, device=device)
+    key = (seed * 7919 + rank * 104729 + 12345) & _M31
+    for lo in range(0, n, block):
+        hi_ = min(n, lo + block)
+        idx = torch.arange(lo, hi_, dtype=torch.int64, device=device)
+        x = (idx ^ key) & _M31
+        for mul, shift in ((1103515245, 13), (214013, 11), (69069, 15)):
+            x = (x * mul + 12345) & _M31
+            x = x ^ (x >> shift)
+        x = ((x ^ ((idx >> 31) & _M31)) * 48271 + 11) & _M31
+        x = x ^ (x >> 16)
+        if dtype == "fp32":
+            out[lo:hi_] = (x >> 7).to(torch.float32) * (2.0 ** -23) - 1.0
+        else:
+            v = (x << 1) & 0xFFFFFFFF
+            out[lo:hi_] = torch.where(v >= (1 << 31), v - (1 << 32), v).to(torch.int32)
+    return out
