@@ -11,6 +11,8 @@
  *                        (paper sections 3.3, 4.1, 4.2.1, 4.2.2)
  *   blink_broadcast /    run the step list on k device buffers, asynchronously
  *   blink_allreduce      on a HIP stream (paper sections 3.3, 4.1)
+ *   blink_miad_*         pick the chunk size over the first iterations of a job
+ *                        (paper section 4.2.1)
  *
  * Conventions
  *   - Every function that can fail returns blink_status_t; results come back
@@ -172,6 +174,25 @@ blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_d
  * device and restarts the schedule's progress counters.  Applies to later
  * calls on this schedule. */
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
+
+/* ---- chunk-size selection across iterations (host only) ---------------------- */
+
+/* Multiplicative-increase, additive-decrease search for the chunk size (paper
+ * section 4.2.1): start at initial_chunk; multiply by factor (> 1) from one
+ * iteration to the next while the reported throughput rises by more than
+ * rel_tol (>= 0, relative); at the first measurement that does not, subtract
+ * step (>= 1) per iteration while that still raises the throughput; then stay
+ * at the best chunk measured.  Chunks are kept inside [lo, hi] (elements, lo >=
+ * 1).  Usage per iteration: make a schedule with blink_miad_chunk(), run and
+ * time the collective, blink_miad_report(throughput, any unit); stop tuning
+ * once blink_miad_steady() is non-zero (further reports change nothing). */
+typedef struct blink_miad blink_miad_t;
+blink_status_t blink_miad_create(size_t initial_chunk, double factor, size_t step, size_t lo,
+                                 size_t hi, double rel_tol, blink_miad_t** out);
+size_t blink_miad_chunk(const blink_miad_t* m);   /* chunk for the next iteration; 0 for a null handle */
+int blink_miad_steady(const blink_miad_t* m);     /* 1 once the search has ended */
+blink_status_t blink_miad_report(blink_miad_t* m, double throughput);
+void blink_miad_free(blink_miad_t* m);
 
 const char* blink_strerror(blink_status_t st);
 

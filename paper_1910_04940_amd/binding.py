@@ -36,7 +36,8 @@ EXPORTS = [
     "blink_schedule_num_steps", "blink_schedule_num_stages", "blink_schedule_num_trees",
     "blink_schedule_get_steps", "blink_schedule_get_bounds", "blink_schedule_traffic_bytes",
     "blink_schedule_free", "blink_allreduce", "blink_broadcast", "blink_schedule_set_launch",
-    "blink_strerror",
+    "blink_strerror", "blink_miad_create", "blink_miad_chunk", "blink_miad_steady",
+    "blink_miad_report", "blink_miad_free",
 ]
 
 
@@ -110,6 +111,14 @@ def lib() -> C.CDLL:
     for name in ("blink_allreduce", "blink_broadcast"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, vp, vp]
     L.blink_schedule_set_launch.argtypes = [vp, C.c_int, C.c_int]
+    L.blink_miad_create.argtypes = [C.c_size_t, C.c_double, C.c_size_t, C.c_size_t, C.c_size_t,
+                                    C.c_double, C.POINTER(vp)]
+    L.blink_miad_chunk.argtypes = [vp]
+    L.blink_miad_chunk.restype = C.c_size_t
+    L.blink_miad_steady.argtypes = [vp]
+    L.blink_miad_report.argtypes = [vp, C.c_double]
+    L.blink_miad_free.argtypes = [vp]
+    L.blink_miad_free.restype = None
     L.blink_strerror.argtypes = [C.c_int]
     L.blink_strerror.restype = C.c_char_p
     _lib = L
@@ -264,3 +273,30 @@ def blink_broadcast(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule
     arr = _pointers(bufs)
     _check(lib().blink_broadcast(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
            "blink_broadcast")
+
+
+class Miad:
+    """Owns a blink_miad_t handle (chunk-size search, paper section 4.2.1)."""
+
+    def __init__(self, initial_chunk: int, factor: float = 2.0, step: int = 0, lo: int = 1,
+                 hi: int = 1 << 40, rel_tol: float = 0.0):
+        out = C.c_void_p()
+        _check(lib().blink_miad_create(initial_chunk, factor, step or initial_chunk, lo, hi, rel_tol,
+                                       C.byref(out)), "blink_miad_create")
+        self._h = out
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.blink_miad_free(self._h)
+            self._h = None
+
+    @property
+    def chunk(self) -> int:
+        return lib().blink_miad_chunk(self._h)
+
+    @property
+    def steady(self) -> bool:
+        return bool(lib().blink_miad_steady(self._h))
+
+    def report(self, throughput: float) -> None:
+        _check(lib().blink_miad_report(self._h, throughput), "blink_miad_report")

@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libblink.so")
-SOURCES = ["api.cpp", "pack.cpp", "schedule.cpp", "exec.hip"]
+SOURCES = ["api.cpp", "pack.cpp", "schedule.cpp", "miad.cpp", "exec.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-c",
     "-fno-gpu-flush-denormals-to-zero",      # fp32 subnormals are ordinary addends

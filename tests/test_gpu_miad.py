@@ -1,0 +1,61 @@
+"""Chunk-size selection (paper section 4.2.1) driving real AllReduce calls: the
+tuner measures the per-edge program, whose speed depends on the chunk size."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import execute as ox
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_1910_04940_amd as bl  # noqa: E402
+
+
+def test_miad_converges_to_a_good_chunk_on_the_edge_program():
+    assert torch.cuda.is_available()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    top = si.hybrid_cube_mesh()
+    n = 1 << 24
+    trees = bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, 0)
+    x = [si.hash_payload(7, r, 0, n, "int32") for r in range(8)]
+    bufs = [torch.from_numpy(a).to(dev) for a in x]
+    stream = torch.cuda.current_stream()
+    calls = 0
+
+    def throughput(chunk):
+        nonlocal calls
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_EDGE)
+        bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream.cuda_stream)       # warm-up, uploads tables
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(4):
+            bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream.cuda_stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        calls += 5
+        return n * 4 / (a.elapsed_time(b) / 4 * 1e-3) / 1e9
+
+    first = 1 << 12                                   # 16 KiB: far too small on purpose
+    tuner = bl.Miad(first, factor=2.0, step=first, lo=1 << 10, hi=n // 4, rel_tol=0.03)
+    tried = []
+    while not tuner.steady and len(tried) < 64:
+        c = tuner.chunk
+        tried.append((c, throughput(c)))
+        tuner.report(tried[-1][1])
+    assert tuner.steady, tried
+    assert [c for c, _ in tried[:3]] == [first, 2 * first, 4 * first]
+    best_seen = max(t for _, t in tried)
+    final = throughput(tuner.chunk)
+    sweep = {c: throughput(c) for c in (1 << 12, 1 << 14, 1 << 16, 1 << 18, 1 << 20, 1 << 22)}
+    print("MIAD tried", tried, "final", tuner.chunk, final, "sweep", sweep)
+    assert final >= 0.8 * best_seen
+    assert final >= 0.8 * max(sweep.values())
+    assert final > 2.0 * tried[0][1]                  # tuning paid off against the starting chunk
+    # every call so far was an exact int32 AllReduce: after `calls` of them each
+    # element is the original sum times 8^(calls-1), modulo 2^32
+    want = ox.allreduce_int32_definition(x).view(np.uint32).astype(np.uint64)
+    want = (want * np.uint64(pow(8, calls - 1, 1 << 32))) & np.uint64(0xFFFFFFFF)
+    got = bufs[5].cpu().numpy().view(np.uint32).astype(np.uint64)
+    assert np.array_equal(got, want)
