@@ -53,7 +53,16 @@ typedef enum {
 } blink_status_t;
 
 typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
-typedef enum { BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1 } blink_op_t;
+/* Collectives (paper section 4.1).  REDUCE is the reduce phase of AllReduce on
+ * its own: afterwards only the root of each tree holds the result (on that
+ * tree's share); what the other ranks' buffers hold is unspecified. */
+typedef enum { BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1, BLINK_OP_REDUCE = 2 } blink_op_t;
+/* Reduction operators (section 4.1 names min and max next to the sum).  SUM and
+ * PROD: one IEEE operation per step for fp32, wrap-around modulo 2^32 for
+ * int32.  MIN and MAX: signed comparison for int32; for fp32 the smaller /
+ * larger under the IEEE total order (-0 below +0), so the result does not
+ * depend on the order of the operands. */
+typedef enum { BLINK_SUM = 0, BLINK_PROD = 1, BLINK_MIN = 2, BLINK_MAX = 3 } blink_redop_t;
 typedef enum { BLINK_STEP_REDUCE = 0, BLINK_STEP_COPY = 1 } blink_step_kind_t;
 
 /* How many tree-edge transfers one wavefront carries a tile through before the
@@ -128,8 +137,9 @@ void blink_trees_free(blink_trees_t* trees);
  * 4.1): share boundaries are floor(n * prefix_weight / total_weight) rounded
  * down to a multiple of 4 elements, exact in rational arithmetic.  Cut every
  * share into chunks of chunk_elems (last one short, section 4.2.1).  Emit, per
- * tree and chunk, one COPY per tree arc and (AllReduce) one REDUCE per reversed
- * arc before them (section 3.3), with their dependencies, ordered so that all
+ * tree and chunk, one COPY per tree arc (Broadcast, AllReduce) and one REDUCE
+ * per reversed arc before them (AllReduce, Reduce; section 3.3), with their
+ * dependencies, ordered so that all
  * trees advance together, one chunk of each in turn (section 4.2.2).
  * A node folds its children in ascending rank id (this fixes the fp32
  * association order).  Broadcast needs all trees to share one root, else
@@ -167,6 +177,14 @@ blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_d
                                blink_schedule_t* s, void* stream);
 blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                                blink_schedule_t* s, void* stream);
+/* AllReduce with another operator (blink_allreduce is this with BLINK_SUM), and
+ * Reduce: the schedule must have been made for BLINK_OP_REDUCE; on completion
+ * the root of each tree holds, on that tree's share, the reduction over all
+ * ranks in tree order. */
+blink_status_t blink_allreduce_op(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                                  blink_redop_t redop, blink_schedule_t* s, void* stream);
+blink_status_t blink_reduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                            blink_redop_t redop, blink_schedule_t* s, void* stream);
 
 /* Launch shape override for tuning: waves per compute unit (0 = automatic) and
  * elements per tile, the unit of work a wave draws at a time (0 = automatic;

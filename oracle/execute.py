@@ -22,20 +22,49 @@ import numpy as np
 from .graph import children_of
 from .schedule import COPY, REDUCE, Step, split_by_weight
 
+# Reduction operators (the paper's section 4.1 names min and max next to the sum
+# and refers to "all the reduction functions" of the library it mirrors).
+SUM, PROD, MIN, MAX = 0, 1, 2, 3
+
+
+def _total_order_key(bits: np.ndarray) -> np.ndarray:
+    """float32 bit patterns -> int32 keys whose signed order is the IEEE total
+    order of the floats (-0 below +0); the map is its own inverse."""
+    i = bits.view(np.int32)
+    return i ^ ((i >> 31) & np.int32(0x7FFFFFFF))
+
+
+def combine(a: np.ndarray, b: np.ndarray, redop: int) -> np.ndarray:
+    """a (+) b element-wise.  a and b are float32, or uint32 views of int32 data.
+    SUM/PROD: one rounded IEEE operation (float) or wrap-around modulo 2^32
+    (integer).  MIN/MAX: the smaller/larger under the IEEE total order for
+    floats (so the result does not depend on operand order even for signed
+    zeros), signed comparison for integers."""
+    if redop == SUM:
+        return a + b
+    if redop == PROD:
+        return a * b
+    if a.dtype == np.float32:
+        ka, kb = _total_order_key(a.view(np.uint32)), _total_order_key(b.view(np.uint32))
+        k = np.minimum(ka, kb) if redop == MIN else np.maximum(ka, kb)
+        return _total_order_key(k.view(np.uint32)).view(np.float32)
+    sa, sb = a.view(np.int32), b.view(np.int32)
+    return (np.minimum(sa, sb) if redop == MIN else np.maximum(sa, sb)).view(np.uint32)
+
 
 def run_steps(bufs: List[np.ndarray], steps: Sequence[Step],
-              order: Optional[Sequence[int]] = None) -> None:
+              order: Optional[Sequence[int]] = None, redop: int = SUM) -> None:
     """Execute the step list in place on the rank buffers (1-D arrays of one
     dtype, float32 or int32).  ``order`` is any topological order of the steps
     (default: list order).  float32 adds round to nearest even once per add;
-    int32 adds wrap modulo 2^32."""
+    int32 adds wrap modulo 2^32; other operators: see ``combine``."""
     is_int = bufs[0].dtype == np.int32
     views = [b.view(np.uint32) for b in bufs] if is_int else bufs
     for i in (range(len(steps)) if order is None else order):
         s = steps[i]
         a, b = s.off, s.off + s.len
         if s.kind == REDUCE:
-            views[s.dst][a:b] = views[s.dst][a:b] + views[s.src][a:b]
+            views[s.dst][a:b] = combine(views[s.dst][a:b], views[s.src][a:b], redop)
         elif s.kind == COPY:
             views[s.dst][a:b] = views[s.src][a:b]
         else:
@@ -43,9 +72,11 @@ def run_steps(bufs: List[np.ndarray], steps: Sequence[Step],
 
 
 def tree_order_allreduce(x: Sequence[np.ndarray], roots: Sequence[int],
-                         trees: Sequence[Sequence[int]], weights: Sequence[float]) -> np.ndarray:
+                         trees: Sequence[Sequence[int]], weights: Sequence[float],
+                         redop: int = SUM) -> np.ndarray:
     """The AllReduce result (identical at every rank) by the recursion over
-    each tree, in the inputs' own dtype.  No chunks, no steps."""
+    each tree, in the inputs' own dtype.  No chunks, no steps.  (For Reduce it
+    is what the root of each tree ends with on that tree's share.)"""
     n = x[0].shape[0]
     is_int = x[0].dtype == np.int32
     xs = [a.view(np.uint32) if is_int else a for a in x]
@@ -58,7 +89,7 @@ def tree_order_allreduce(x: Sequence[np.ndarray], roots: Sequence[int],
         def S(v: int) -> np.ndarray:
             acc = xs[v][lo:hi].copy()
             for c in ch[v]:
-                acc = acc + S(c)
+                acc = combine(acc, S(c), redop)
             return acc
 
         out[lo:hi] = S(root)
@@ -71,6 +102,29 @@ def allreduce_int32_definition(x: Sequence[np.ndarray]) -> np.ndarray:
     for a in x:
         acc += a.view(np.uint32)
     return (acc & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.int32)
+
+
+def reduce_definition(x: Sequence[np.ndarray], redop: int) -> np.ndarray:
+    """Order-free operators written out as plain definitions: int32 SUM and PROD
+    modulo 2^32 in unbounded Python-width arithmetic, MIN and MAX as the
+    element-wise extreme (IEEE total order for float32).  float32 SUM and PROD
+    have no order-free definition and are refused."""
+    is_int = x[0].dtype == np.int32
+    if redop in (MIN, MAX):
+        if is_int:
+            st = np.stack(x)
+            return st.min(axis=0) if redop == MIN else st.max(axis=0)
+        keys = np.stack([_total_order_key(a.view(np.uint32)) for a in x])
+        k = keys.min(axis=0) if redop == MIN else keys.max(axis=0)
+        return _total_order_key(k.view(np.uint32)).view(np.float32)
+    if not is_int:
+        raise ValueError("float32 sum/product depend on the association order")
+    if redop == SUM:
+        return allreduce_int32_definition(x)
+    acc = np.ones(x[0].shape[0], np.uint64)
+    for a in x:
+        acc = (acc * a.view(np.uint32).astype(np.uint64)) & np.uint64(0xFFFFFFFF)
+    return acc.astype(np.uint32).view(np.int32)
 
 
 def allreduce_exact_f64(x: Sequence[np.ndarray]) -> np.ndarray:

@@ -39,6 +39,7 @@ COPY = 1    # dst[off:off+len] <- src[off:off+len]
 
 BROADCAST = 0
 ALLREDUCE = 1
+REDUCE_TO_ROOT = 2   # the reduce phase alone: only the tree roots end with the result
 
 
 @dataclass(frozen=True)
@@ -126,7 +127,7 @@ def make_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
         for c, (off, ln) in enumerate(chunk_ranges(bounds[t], bounds[t + 1], chunk)):
             red: Dict[int, int] = {}   # vertex -> index of its REDUCE-out step
             cp: Dict[int, int] = {}    # vertex -> index of the COPY into it
-            if op == ALLREDUCE:
+            if op in (ALLREDUCE, REDUCE_TO_ROOT):
                 for v in reduce_order(root, parent):
                     p = parent[v]
                     deps = []
@@ -137,7 +138,7 @@ def make_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
                         deps.append(red[ch[p][i - 1]])
                     red[v] = len(steps)
                     steps.append(Step(REDUCE, t, c, v, p, off, ln, tuple(deps)))
-            for v in broadcast_order(root, parent):
+            for v in (broadcast_order(root, parent) if op != REDUCE_TO_ROOT else []):
                 p = parent[v]
                 if p != root:
                     deps = (cp[p],)
@@ -173,12 +174,14 @@ def check_steps(steps: Sequence[Step], k: int, roots: Sequence[int],
     """Structural checks on a step list produced by anyone:
       * dependencies point backwards (hence the graph is acyclic);
       * per tree the chunks tile the tree's share exactly once;
-      * per (tree, chunk): exactly one COPY per tree arc parent->child and, for
-        AllReduce, exactly one REDUCE per reversed arc child->parent;
+      * per (tree, chunk): exactly one COPY per tree arc parent->child
+        (Broadcast, AllReduce) and exactly one REDUCE per reversed arc
+        child->parent (AllReduce, Reduce);
       * replaying the list in order with symbolic contents gives, at every
         rank, the tree-order sum over all ranks (AllReduce) or the root's
-        value (Broadcast), and every step reads only values its listed
-        dependencies (transitively) made final."""
+        value (Broadcast), or the tree-order sum at the root (Reduce), and every
+        step reads only values its listed dependencies (transitively) made
+        final."""
     bounds = split_by_weight(n, weights)
     for i, s in enumerate(steps):
         assert all(0 <= d < i for d in s.deps), f"step {i}: dependency not earlier"
@@ -198,8 +201,9 @@ def check_steps(steps: Sequence[Step], k: int, roots: Sequence[int],
             assert all(steps[i].off == off and steps[i].len == ln for i in ix)
             copies = sorted((steps[i].src, steps[i].dst) for i in ix if steps[i].kind == COPY)
             reduces = sorted((steps[i].dst, steps[i].src) for i in ix if steps[i].kind == REDUCE)
-            assert copies == arcs, f"tree {t} chunk {c}: COPY steps do not match the tree arcs"
-            assert reduces == (arcs if op == ALLREDUCE else []), \
+            assert copies == (arcs if op != REDUCE_TO_ROOT else []), \
+                f"tree {t} chunk {c}: COPY steps do not match the tree arcs"
+            assert reduces == (arcs if op != BROADCAST else []), \
                 f"tree {t} chunk {c}: REDUCE steps do not match the reversed tree arcs"
             _symbolic_replay(steps, ix, k, root, parent, op)
 
@@ -242,8 +246,8 @@ def _symbolic_replay(steps, idx, k, root, parent, op) -> None:
             val[s.dst] = (val[s.src][0], i)
         readers[s.dst] = []
         readers[s.src].append(i)
-    want = _tree_order_expr(root, ch) if op == ALLREDUCE else ("x", root)
-    for v in range(k):
+    want = _tree_order_expr(root, ch) if op != BROADCAST else ("x", root)
+    for v in (range(k) if op != REDUCE_TO_ROOT else [root]):
         assert val[v][0] == want, f"rank {v} ends with {val[v][0]}, expected {want}"
 
 

@@ -135,14 +135,28 @@ void blink_schedule_free(blink_schedule_t* s) {
 blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                                blink_schedule_t* s, void* stream) {
     BLINK_GUARD_BEGIN
-    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, stream);
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, BLINK_SUM, stream);
     BLINK_GUARD_END
 }
 
 blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                                blink_schedule_t* s, void* stream) {
     BLINK_GUARD_BEGIN
-    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_BROADCAST, stream);
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_BROADCAST, BLINK_SUM, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_allreduce_op(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                                  blink_redop_t redop, blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, redop, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_reduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                            blink_redop_t redop, blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_REDUCE, redop, stream);
     BLINK_GUARD_END
 }
 

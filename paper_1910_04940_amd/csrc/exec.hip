@@ -32,6 +32,7 @@
 #include <algorithm>
 #include <cstddef>
 #include <cstdio>
+#include <type_traits>
 #include <vector>
 
 #include "schedule.hpp"
@@ -64,6 +65,7 @@ struct KParams {
     unsigned long long epoch;
     unsigned tiles_per_chunk;
     unsigned tile_shift;  // a tile is 2^tile_shift elements
+    unsigned redop;       // blink_redop_t
     unsigned group;  // consecutive instances whose tiles are handed out in turn (1 = instance by instance)
 };
 
@@ -78,28 +80,46 @@ using ConstInst = const BLINK_CONST StageInst*;
 typedef float F4 __attribute__((ext_vector_type(4)));
 typedef unsigned U4 __attribute__((ext_vector_type(4)));  // one 128-bit access, as raw bits
 
-// Element-wise add on raw bits.  fp32: one IEEE add per element (round to
-// nearest even, subnormals kept).  int32: unsigned add, i.e. wrap-around
-// modulo 2^32 without signed-overflow UB.
+// Element-wise a (+) b on raw bits; `op` is wave-uniform.  fp32 SUM / PROD: one
+// IEEE operation per element (round to nearest even, subnormals kept).  int32
+// SUM / PROD: unsigned arithmetic, i.e. wrap-around modulo 2^32 without
+// signed-overflow UB.  MIN / MAX: signed comparison for int32; for fp32 the
+// bits are mapped to keys whose signed order is the IEEE total order (-0 below
+// +0; the map is its own inverse), so min and max commute bit for bit.
 template <typename T>
-__device__ __forceinline__ U4 vadd(U4 a, U4 b);
+__device__ __forceinline__ unsigned combine1(unsigned op, unsigned a, unsigned b);
 template <>
-__device__ __forceinline__ U4 vadd<float>(U4 a, U4 b) {
-    return __builtin_bit_cast(U4, __builtin_bit_cast(F4, a) + __builtin_bit_cast(F4, b));
+__device__ __forceinline__ unsigned combine1<float>(unsigned op, unsigned a, unsigned b) {
+    if (op == BLINK_SUM)
+        return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b));
+    if (op == BLINK_PROD)
+        return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) * __builtin_bit_cast(float, b));
+    const int ka = static_cast<int>(a) ^ ((static_cast<int>(a) >> 31) & 0x7fffffff);
+    const int kb = static_cast<int>(b) ^ ((static_cast<int>(b) >> 31) & 0x7fffffff);
+    const int k = op == BLINK_MIN ? min(ka, kb) : max(ka, kb);
+    return static_cast<unsigned>(k ^ ((k >> 31) & 0x7fffffff));
 }
 template <>
-__device__ __forceinline__ U4 vadd<unsigned>(U4 a, U4 b) {
-    return a + b;
+__device__ __forceinline__ unsigned combine1<unsigned>(unsigned op, unsigned a, unsigned b) {
+    if (op == BLINK_SUM) return a + b;
+    if (op == BLINK_PROD) return a * b;
+    const int sa = static_cast<int>(a), sb = static_cast<int>(b);
+    return static_cast<unsigned>(op == BLINK_MIN ? min(sa, sb) : max(sa, sb));
 }
 template <typename T>
-__device__ __forceinline__ unsigned sadd(unsigned a, unsigned b);
-template <>
-__device__ __forceinline__ unsigned sadd<float>(unsigned a, unsigned b) {
-    return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b));
-}
-template <>
-__device__ __forceinline__ unsigned sadd<unsigned>(unsigned a, unsigned b) {
-    return a + b;
+__device__ __forceinline__ U4 combine4(unsigned op, U4 a, U4 b) {
+    if (op == BLINK_SUM) {  // the common case, kept free of per-element selects
+        if constexpr (std::is_same<T, float>::value)
+            return __builtin_bit_cast(U4, __builtin_bit_cast(F4, a) + __builtin_bit_cast(F4, b));
+        else
+            return a + b;
+    }
+    U4 r;
+    r.x = combine1<T>(op, a.x, b.x);
+    r.y = combine1<T>(op, a.y, b.y);
+    r.z = combine1<T>(op, a.z, b.z);
+    r.w = combine1<T>(op, a.w, b.w);
+    return r;
 }
 
 // Byte `field_offset + i` of a stage template, fetched as part of a 32-bit word
@@ -130,6 +150,7 @@ template <typename T, int N, int U, int LD, int ST>
 __device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
                                         unsigned long long byte_off, unsigned bytes, int lane) {
     constexpr unsigned kSubBytes = kLanes * U * 16;
+    const unsigned redop = p->redop;
     const int n_op = BLINK_TMPL(st, n_op, 0);
     const int n_store = BLINK_TMPL(st, n_store, 0);
     for (unsigned b = 0; b < bytes; b += kSubBytes) {
@@ -158,7 +179,7 @@ __device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, C
                 for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
             } else if (kind == OP_ADD) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] = vadd<T>(acc[u], sl[u * kLanes]);
+                for (int u = 0; u < U; ++u) acc[u] = combine4<T>(redop, acc[u], sl[u * kLanes]);
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
@@ -216,6 +237,7 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
         slots[i * kLanes + lane] = __builtin_amdgcn_raw_buffer_load_b32(win, lane * 4, 0, LD);
     }
     unsigned acc = 0;
+    const unsigned redop = p->redop;
     const int n_op = BLINK_TMPL(st, n_op, 0);
     for (int o = 0; o < n_op; ++o) {
         const unsigned code = BLINK_TMPL(st, op, o);
@@ -224,7 +246,7 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
         if (kind == OP_LD)
             acc = *sl;
         else if (kind == OP_ADD)
-            acc = sadd<T>(acc, *sl);
+            acc = combine1<T>(redop, acc, *sl);
         else
             *sl = acc;
     }
@@ -431,9 +453,10 @@ void release_device_state(blink_schedule* h) {
 }
 
 blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, blink_dtype_t dtype,
-                       blink_op_t op, void* stream) {
+                       blink_op_t op, blink_redop_t redop, void* stream) {
     if (!h || !bufs) return BLINK_EINVAL;
     if (dtype != BLINK_FP32 && dtype != BLINK_INT32) return BLINK_EINVAL;
+    if (redop != BLINK_SUM && redop != BLINK_PROD && redop != BLINK_MIN && redop != BLINK_MAX) return BLINK_EINVAL;
     const Schedule& s = h->s;
     if (k != s.k || n != s.n || op != s.op) return BLINK_EMISMATCH;
     for (int i = 0; i < k; ++i) {
@@ -508,6 +531,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.epoch = ++h->epoch;
     p.tiles_per_chunk = static_cast<unsigned>(tiles_per_chunk);
     p.tile_shift = tile_shift;
+    p.redop = static_cast<unsigned>(redop);
     // Without dependencies the order of tiles is free: interleave the trees tile by tile.
     p.group = s.has_deps ? 1u : static_cast<unsigned>(s.n_trees);
     hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), 0,

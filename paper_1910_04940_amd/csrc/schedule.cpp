@@ -71,7 +71,7 @@ std::vector<StageTmpl> edge_stages(int k, int root, const ParentVec& parent, bli
     const auto ch = children(k, parent);
     std::vector<StageTmpl> out;
     std::vector<int> red(k, -1), cp(k, -1);
-    if (op == BLINK_OP_ALLREDUCE) {
+    if (op != BLINK_OP_BROADCAST) {
         std::function<void(int)> visit = [&](int v) {
             for (int c : ch[v]) visit(c);
             if (v == root) return;
@@ -94,6 +94,7 @@ std::vector<StageTmpl> edge_stages(int k, int root, const ParentVec& parent, bli
         };
         visit(root);
     }
+    if (op == BLINK_OP_REDUCE) return out;
     std::vector<int> frontier{root};
     while (!frontier.empty()) {
         std::vector<int> next;
@@ -125,7 +126,7 @@ std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, bli
     const auto ch = children(k, parent);
     std::vector<StageTmpl> out;
     std::vector<int> fin(k, -1), fout(k, -1);
-    if (op == BLINK_OP_ALLREDUCE) {
+    if (op != BLINK_OP_BROADCAST) {
         std::function<void(int)> visit = [&](int v) {
             for (int c : ch[v]) visit(c);
             if (ch[v].empty()) return;
@@ -138,7 +139,7 @@ std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, bli
                 if (!ch[c].empty()) t.dep_local[t.n_dep++] = static_cast<uint8_t>(fin[c]);
             }
             t.store_rank[t.n_store++] = static_cast<uint8_t>(v);
-            if (v == root)
+            if (v == root && op == BLINK_OP_ALLREDUCE)
                 for (int c : ch[v]) t.store_rank[t.n_store++] = static_cast<uint8_t>(c);
             fin[v] = static_cast<int>(out.size());
             out.push_back(t);
@@ -146,6 +147,7 @@ std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, bli
         visit(root);
         fout[root] = fin[root];
     }
+    if (op == BLINK_OP_REDUCE) return out;
     std::vector<int> frontier{root};
     while (!frontier.empty()) {
         std::vector<int> next;
@@ -171,7 +173,8 @@ std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, bli
 
 // acc <- S(v) = ((x_v + S(c_1)) + S(c_2)) + ..., children ascending.  Slot i
 // holds x_i.  The first child's sum is formed first and x_v added to it (IEEE
-// addition commutes, so the bits equal x_v + S(c_1)); before a later child
+// addition and multiplication commute bit for bit, and min/max are taken under
+// a total order, so the bits equal x_v (+) S(c_1)); before a later child
 // that has children of its own the running sum is parked in v's slot, which is
 // free once x_v has been consumed.
 void eval_tree(int v, const std::vector<std::vector<int>>& ch, StageTmpl& t) {
@@ -196,10 +199,13 @@ void eval_tree(int v, const std::vector<std::vector<int>>& ch, StageTmpl& t) {
 // The whole tree in one stage: every rank read once and written once.
 std::vector<StageTmpl> tree_stage(int k, int root, const ParentVec& parent, blink_op_t op) {
     StageTmpl t = blank();
-    if (op == BLINK_OP_ALLREDUCE) {
+    if (op != BLINK_OP_BROADCAST) {
         for (int v = 0; v < k; ++v) t.load_rank[t.n_load++] = static_cast<uint8_t>(v);
         eval_tree(root, children(k, parent), t);
-        for (int v = 0; v < k; ++v) t.store_rank[t.n_store++] = static_cast<uint8_t>(v);
+        if (op == BLINK_OP_REDUCE)
+            t.store_rank[t.n_store++] = static_cast<uint8_t>(root);
+        else
+            for (int v = 0; v < k; ++v) t.store_rank[t.n_store++] = static_cast<uint8_t>(v);
     } else {
         t.n_load = 1;
         t.load_rank[0] = static_cast<uint8_t>(root);
@@ -331,7 +337,7 @@ blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint
     const int T = trees.count(), k = trees.k;
     if (T < 1 || k < 2 || k > BLINK_MAX_RANKS || chunk == 0) return BLINK_EINVAL;
     if (chunk > 0xFFFFFFFFull) chunk = 0xFFFFFFFFull - 3;  // a chunk is addressed with 32 bits
-    if (op != BLINK_OP_ALLREDUCE && op != BLINK_OP_BROADCAST) return BLINK_EINVAL;
+    if (op != BLINK_OP_ALLREDUCE && op != BLINK_OP_BROADCAST && op != BLINK_OP_REDUCE) return BLINK_EINVAL;
     if (fusion != BLINK_FUSE_EDGE && fusion != BLINK_FUSE_NODE && fusion != BLINK_FUSE_TREE)
         return BLINK_EINVAL;
     if (op == BLINK_OP_BROADCAST)

@@ -24,7 +24,7 @@ struct blink_schedule {
 
 namespace blink {
 blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, blink_dtype_t dtype,
-                       blink_op_t op, void* stream);
+                       blink_op_t op, blink_redop_t redop, void* stream);
 blink_status_t reset_progress(blink_schedule* h);
 void release_device_state(blink_schedule* h);
 }  // namespace blink

@@ -274,3 +274,67 @@ def test_non_default_stream(dev):
     want = ox.allreduce_int32_definition(x)
     for b in bufs:
         assert np.array_equal(b.cpu().numpy(), want)
+
+
+# ---- other reduction operators and the Reduce collective -----------------------------------
+REDOPS = {"prod": (bl.BLINK_PROD, ox.PROD), "min": (bl.BLINK_MIN, ox.MIN), "max": (bl.BLINK_MAX, ox.MAX),
+          "sum": (bl.BLINK_SUM, ox.SUM)}
+
+
+@pytest.mark.parametrize("redop", ["prod", "min", "max"])
+@pytest.mark.parametrize("fusion", FUSIONS)
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+def test_allreduce_with_other_operators(dev, redop, fusion, dtype):
+    top = si.hybrid_cube_mesh()
+    n, chunk = 150_003, 16_384
+    trees = pack(top, 0)
+    roots, parents, w = trees.as_lists()
+    if dtype == "fp32":
+        # products of 8 numbers near 1 neither overflow nor vanish; signed zeros for min / max
+        x = [(si.payload(81, r, n, "uniform", "fp32") * np.float32(0.5) + np.float32(1.0)).astype(np.float32)
+             for r in range(8)]
+        if redop != "prod":
+            x = [si.payload(81, r, n, "uniform", "fp32") for r in range(8)]
+            x[2][::5] = -0.0
+            x[6][::5] = 0.0
+            for r in (0, 1, 3, 4, 5, 7):
+                x[r][::5] = np.float32(0.0) if redop == "min" else np.float32(-0.0)
+    else:
+        x = [si.payload(82, r, n, "int", "int32") for r in range(8)]
+    want = [a.copy() for a in x]
+    ox.run_steps(want, osch.make_steps(roots, parents, w, osch.ALLREDUCE, n, chunk), redop=REDOPS[redop][1])
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    code = bl.BLINK_INT32 if dtype == "int32" else bl.BLINK_FP32
+    bl.blink_allreduce_op(bufs, n, code, REDOPS[redop][0], sched, stream())
+    torch.cuda.synchronize()
+    for r, b in enumerate(bufs):
+        assert b.cpu().numpy().tobytes() == want[r].tobytes(), f"{redop} {dtype} fusion {fusion} rank {r}"
+    if redop != "prod" or dtype == "int32":
+        assert want[0].tobytes() == ox.reduce_definition(x, REDOPS[redop][1]).tobytes()
+
+
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.chain(6), 3), (si.complete_graph(16), bl.BLINK_ROOT_ANY)])
+@pytest.mark.parametrize("fusion", FUSIONS)
+@pytest.mark.parametrize("redop", ["sum", "max"])
+def test_reduce_to_the_roots(dev, top, root, fusion, redop):
+    n, chunk = 120_002, 8_192
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    x = [si.payload(91, r, n, "uniform", "fp32") for r in range(top.k)]
+    want = ox.tree_order_allreduce(x, roots, parents, w, REDOPS[redop][1])
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_REDUCE, n, chunk, fusion)
+    bl.blink_reduce(bufs, n, bl.BLINK_FP32, REDOPS[redop][0], sched, stream())
+    torch.cuda.synchronize()
+    b = sched.bounds()
+    for t, r in enumerate(roots):                      # tree t's share ends up at tree t's root
+        got = bufs[r][b[t]:b[t + 1]].cpu().numpy()
+        assert got.tobytes() == want[b[t]:b[t + 1]].tobytes(), f"tree {t} root {r}"
+    # a schedule made for Reduce cannot run an AllReduce
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+    assert e.value.status == bl.BLINK_EMISMATCH
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_reduce(bufs, n, bl.BLINK_FP32, 9, sched, stream())
+    assert e.value.status == bl.BLINK_EINVAL

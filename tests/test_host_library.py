@@ -152,7 +152,7 @@ SCHED_CASES = [
 
 
 @pytest.mark.parametrize("top,root,n,chunk", SCHED_CASES)
-@pytest.mark.parametrize("coll", [bl.BLINK_OP_ALLREDUCE, bl.BLINK_OP_BROADCAST])
+@pytest.mark.parametrize("coll", [bl.BLINK_OP_ALLREDUCE, bl.BLINK_OP_BROADCAST, bl.BLINK_OP_REDUCE])
 @pytest.mark.parametrize("fusion", [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE])
 def test_schedule_passes_oracle_validators(top, root, n, chunk, coll, fusion):
     trees = pack(top, root)
@@ -160,19 +160,21 @@ def test_schedule_passes_oracle_validators(top, root, n, chunk, coll, fusion):
     sched = bl.blink_make_schedule(trees, coll, n, chunk, fusion)
     assert sched.bounds() == osch.split_by_weight(n, w)
     steps = to_oracle_steps(sched)
-    ocoll = osch.ALLREDUCE if coll == bl.BLINK_OP_ALLREDUCE else osch.BROADCAST
+    ocoll = {bl.BLINK_OP_ALLREDUCE: osch.ALLREDUCE, bl.BLINK_OP_BROADCAST: osch.BROADCAST,
+             bl.BLINK_OP_REDUCE: osch.REDUCE_TO_ROOT}[coll]
     osch.check_steps(steps, top.k, roots, parents, w, ocoll, n, chunk)
     assert len(steps) == len(osch.make_steps(roots, parents, w, ocoll, n, chunk))
     # analytic traffic of the three fusion levels (4-byte elements)
     k = top.k
     if fusion == bl.BLINK_FUSE_EDGE:
-        per = 20 * (k - 1) if coll == bl.BLINK_OP_ALLREDUCE else 8 * (k - 1)
+        per = {bl.BLINK_OP_ALLREDUCE: 20 * (k - 1), bl.BLINK_OP_BROADCAST: 8 * (k - 1),
+               bl.BLINK_OP_REDUCE: 12 * (k - 1)}[coll]
         assert sched.traffic_bytes == per * n and sched.num_stages == len(steps)
     if fusion == bl.BLINK_FUSE_TREE:
-        per = 8 * k if coll == bl.BLINK_OP_ALLREDUCE else 4 * k
+        per = {bl.BLINK_OP_ALLREDUCE: 8 * k, bl.BLINK_OP_BROADCAST: 4 * k, bl.BLINK_OP_REDUCE: 4 * k + 4}[coll]
         assert sched.traffic_bytes == per * n
         assert sched.num_stages == len({(s.tree, s.chunk) for s in steps})
-    if fusion == bl.BLINK_FUSE_NODE:
+    if fusion == bl.BLINK_FUSE_NODE and coll != bl.BLINK_OP_REDUCE:
         b = sched.bounds()
         want = 0
         for t, parent in enumerate(parents):

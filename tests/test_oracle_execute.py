@@ -165,3 +165,67 @@ def test_a_dropped_dependency_changes_some_valid_looking_execution():
         ox.run_steps(bufs, broken, ox.random_topological_order(broken, seed))
         wrong += not np.array_equal(bufs[0], want)
     assert wrong > 0
+
+
+# ---- other reduction operators and the Reduce collective --------------------------------
+@pytest.mark.parametrize("redop", [ox.PROD, ox.MIN, ox.MAX])
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+def test_other_operators_against_plain_definitions(redop, dtype):
+    top = si.hybrid_cube_mesh()
+    roots, trees, w = make(top)
+    n, chunk = 20_001, 3000
+    x = inputs(8, n, dtype, seed=12)
+    if dtype == "fp32":
+        x[3][::7] = -0.0
+        x[5][::7] = 0.0          # signed zeros: MIN must give -0, MAX +0, whatever the order
+    bufs = [a.copy() for a in x]
+    steps = osch.make_steps(roots, trees, w, osch.ALLREDUCE, n, chunk)
+    ox.run_steps(bufs, steps, ox.random_topological_order(steps, 3), redop=redop)
+    rec = ox.tree_order_allreduce(x, roots, trees, w, redop)
+    for b in bufs:
+        assert b.tobytes() == rec.tobytes()
+    if redop in (ox.MIN, ox.MAX) or dtype == "int32":
+        assert rec.tobytes() == ox.reduce_definition(x, redop).tobytes()
+    if redop in (ox.MIN, ox.MAX):
+        # element by element against Python's min/max on a sample
+        st = np.stack(x)
+        for j in range(0, n, 501):
+            col = [v.item() for v in st[:, j]]
+            assert rec[j] == (min(col) if redop == ox.MIN else max(col))
+        if dtype == "fp32":
+            col = np.stack([a[::7] for a in x])
+            only_zeros_extreme = (col.min(axis=0) == 0) if redop == ox.MIN else (col.max(axis=0) == 0)
+            sign = np.signbit(rec[::7][only_zeros_extreme])
+            assert sign.all() if redop == ox.MIN else (~sign).all()
+    else:
+        # float product: within k-1 roundings of the float64 product
+        if dtype == "fp32":
+            exact = np.prod(np.stack(x).astype(np.float64), axis=0)
+            assert np.allclose(rec.astype(np.float64), exact, rtol=8 * 2.0 ** -24, atol=1e-45)
+
+
+def test_int32_product_wraps():
+    x = [np.array([65537, -3, 7], np.int32), np.array([65537, 5, -7], np.int32)]
+    got = ox.reduce_definition(x, ox.PROD)
+    assert got.tolist() == [(65537 * 65537) % (1 << 32) - 0 if (65537 * 65537) % (1 << 32) < (1 << 31)
+                            else (65537 * 65537) % (1 << 32) - (1 << 32), -15, -49]
+    assert ox.combine(x[0].view(np.uint32), x[1].view(np.uint32), ox.PROD).view(np.int32).tolist() == got.tolist()
+
+
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.chain(5), 2), (si.complete_graph(4), 1)])
+def test_reduce_to_root(top, root):
+    roots, trees, w = make(top, root)
+    n, chunk = 9_999, 1024
+    x = inputs(top.k, n, "fp32", seed=13)
+    bufs = [a.copy() for a in x]
+    steps = osch.make_steps(roots, trees, w, osch.REDUCE_TO_ROOT, n, chunk)
+    osch.check_steps(steps, top.k, roots, trees, w, osch.REDUCE_TO_ROOT, n, chunk)
+    assert all(s.kind == osch.REDUCE for s in steps)
+    ox.run_steps(bufs, steps, ox.random_topological_order(steps, 2))
+    want = ox.tree_order_allreduce(x, roots, trees, w)
+    assert bufs[root].tobytes() == want.tobytes()
+    # leaves are untouched by a Reduce
+    ch = og.children_of(trees[0])
+    leaves_everywhere = [v for v in range(top.k) if all(not og.children_of(t)[v] for t in trees)]
+    for v in leaves_everywhere:
+        assert bufs[v].tobytes() == x[v].tobytes()
