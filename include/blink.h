@@ -56,7 +56,18 @@ typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
 /* Collectives (paper section 4.1).  REDUCE is the reduce phase of AllReduce on
  * its own: afterwards only the root of each tree holds the result (on that
  * tree's share); what the other ranks' buffers hold is unspecified. */
-typedef enum { BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1, BLINK_OP_REDUCE = 2 } blink_op_t;
+/* ALLGATHER and GATHER work on buffers of n_elems = k * m elements in which rank
+ * j owns piece j = [j*m, (j+1)*m) and starts with it in place: afterwards every
+ * rank (ALLGATHER) or the root of each tree (GATHER, on that tree's share of
+ * every piece) holds all k pieces.  "Gather is the inverse of Broadcast, and
+ * AllGather is AllReduce without a reduction": every piece is split among the
+ * trees by weight; a tree moves its share of piece j hop by hop along its own
+ * edges, away from rank j in every direction (ALLGATHER) or up to its root
+ * (GATHER). */
+typedef enum {
+    BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1, BLINK_OP_REDUCE = 2,
+    BLINK_OP_ALLGATHER = 3, BLINK_OP_GATHER = 4
+} blink_op_t;
 /* Reduction operators (section 4.1 names min and max next to the sum).  SUM and
  * PROD: one IEEE operation per step for fp32, wrap-around modulo 2^32 for
  * int32.  MIN and MAX: signed comparison for int32; for fp32 the smaller /
@@ -185,6 +196,14 @@ blink_status_t blink_allreduce_op(void* const* bufs, int k, size_t n_elems, blin
                                   blink_redop_t redop, blink_schedule_t* s, void* stream);
 blink_status_t blink_reduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                             blink_redop_t redop, blink_schedule_t* s, void* stream);
+/* AllGather / Gather; the schedule must have been made for BLINK_OP_ALLGATHER /
+ * BLINK_OP_GATHER with the same n_elems (a multiple of k, else
+ * blink_make_schedule returns BLINK_EINVAL).  For these two collectives
+ * blink_schedule_get_bounds returns the split of one piece (n_elems / k). */
+blink_status_t blink_allgather(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream);
+blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                            blink_schedule_t* s, void* stream);
 
 /* Launch shape override for tuning: waves per compute unit (0 = automatic) and
  * elements per tile, the unit of work a wave draws at a time (0 = automatic;

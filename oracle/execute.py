@@ -171,3 +171,11 @@ def random_topological_order(steps: Sequence[Step], seed: int) -> List[int]:
                 ready.append(u)
     assert len(out) == n
     return out
+
+
+def allgather_definition(x: Sequence[np.ndarray]) -> np.ndarray:
+    """Concatenation of the pieces: with k buffers of k*m elements, piece j is
+    x[j][j*m:(j+1)*m]."""
+    k = len(x)
+    m = x[0].shape[0] // k
+    return np.concatenate([x[j][j * m:(j + 1) * m] for j in range(k)])

@@ -40,6 +40,8 @@ COPY = 1    # dst[off:off+len] <- src[off:off+len]
 BROADCAST = 0
 ALLREDUCE = 1
 REDUCE_TO_ROOT = 2   # the reduce phase alone: only the tree roots end with the result
+ALLGATHER = 3        # every rank ends with the concatenation of all ranks' pieces
+GATHER = 4           # only the tree roots do
 
 
 @dataclass(frozen=True)
@@ -149,6 +151,132 @@ def make_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
                 cp[v] = len(steps)
                 steps.append(Step(COPY, t, c, p, v, off, ln, deps))
     return steps
+
+
+# --------------------------------------------------------------------------
+# Gather and AllGather (section 4.1: "Gather is the inverse of Broadcast, and
+# AllGather is AllReduce without using a reduction function")
+# --------------------------------------------------------------------------
+# Every rank buffer has n = k * m elements; rank j owns piece j = [j*m, (j+1)*m)
+# and starts with it in place.  Each piece is split among the trees by weight
+# like any payload, and tree t moves its share of piece j along its own edges:
+#   * AllReduce without a reduction: what travels up to the root and back down
+#     is the data itself, so piece j simply spreads from rank j over the
+#     (undirected) tree, hop by hop, each rank forwarding a chunk once it has
+#     all of it: a broadcast along the tree re-rooted at j;
+#   * Gather: piece j climbs from rank j to the tree's root along the reverse of
+#     the path Broadcast would use to reach j.
+def reroot(parent: Sequence[int], new_root: int) -> Tuple[int, ...]:
+    """The same undirected tree with every edge directed away from new_root."""
+    k = len(parent)
+    nbrs: List[List[int]] = [[] for _ in range(k)]
+    for v, p in enumerate(parent):
+        if p >= 0:
+            nbrs[v].append(p)
+            nbrs[p].append(v)
+    out = [-2] * k
+    out[new_root] = -1
+    stack = [new_root]
+    while stack:
+        u = stack.pop()
+        for v in nbrs[u]:
+            if out[v] == -2:
+                out[v] = u
+                stack.append(v)
+    return tuple(out)
+
+
+def climb(parent: Sequence[int], j: int) -> Tuple[int, ...]:
+    """Flow of piece j towards the root of ``parent``: j first, then its
+    ancestors, each receiving from the one below; ranks off the path take no
+    part (-2)."""
+    out = [-2] * len(parent)
+    out[j] = -1
+    v = j
+    while parent[v] >= 0:
+        out[parent[v]] = v
+        v = parent[v]
+    return tuple(out)
+
+
+def make_gather_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
+                      weights: Sequence[float], op: int, n: int, chunk: int) -> List[Step]:
+    """Step list of AllGather / Gather on buffers of n = k*m elements: only COPY
+    steps; a COPY u->v of a piece's chunk waits for the COPY that brought that
+    chunk into u (none when u owns the piece)."""
+    k = len(trees[0])
+    if n % k:
+        raise ValueError("the buffer length must be a multiple of the number of ranks")
+    m = n // k
+    bounds = split_by_weight(m, weights)
+    steps: List[Step] = []
+    for t, (root, parent) in enumerate(zip(roots, trees)):
+        for j in range(k):
+            flow = reroot(parent, j) if op == ALLGATHER else climb(parent, j)
+            lo, hi = j * m + bounds[t], j * m + bounds[t + 1]
+            for c, (off, ln) in enumerate(chunk_ranges(lo, hi, chunk)):
+                into: Dict[int, int] = {}
+                for v in broadcast_order(j, [p if p >= 0 else -1 for p in flow]):
+                    p = flow[v]
+                    deps = (into[p],) if p != j else ()
+                    into[v] = len(steps)
+                    steps.append(Step(COPY, t, c, p, v, off, ln, deps))
+    return steps
+
+
+def check_gather_steps(steps: Sequence[Step], k: int, roots: Sequence[int],
+                       trees: Sequence[Sequence[int]], weights: Sequence[float], op: int,
+                       n: int, chunk: int) -> None:
+    """For any scheduler's AllGather / Gather list: dependencies point backwards;
+    per tree and piece the chunks tile the tree's share of the piece; every step
+    is a COPY over a tree edge (either direction); replaying with symbolic
+    contents, every step forwards a chunk its dependencies have delivered, and
+    at the end every rank (AllGather) or the tree's root (Gather) holds piece
+    j's data there, each rank having received it exactly once."""
+    assert n % k == 0
+    m = n // k
+    bounds = split_by_weight(m, weights)
+    for i, s in enumerate(steps):
+        assert s.kind == COPY and all(0 <= d < i for d in s.deps)
+    groups: Dict[Tuple[int, int, int], List[int]] = {}
+    for i, s in enumerate(steps):
+        groups.setdefault((s.tree, s.off // m if m else 0, s.chunk), []).append(i)
+    for t, (root, parent) in enumerate(zip(roots, trees)):
+        edges = {(parent[v], v) for v in range(k) if v != root} | {(v, parent[v]) for v in range(k) if v != root}
+        for j in range(k):
+            want = chunk_ranges(j * m + bounds[t], j * m + bounds[t + 1], chunk)
+            if op == GATHER and j == root:
+                want = []                          # the root's own piece is already in place
+            got = sorted({(steps[ix[0]].off, steps[ix[0]].len) for (tt, jj, _), ix in groups.items()
+                          if tt == t and jj == j})
+            assert got == want, f"tree {t} piece {j}: chunks {got[:2]} do not tile {want[:2]}"
+            for (tt, jj, c), ix in groups.items():
+                if (tt, jj) != (t, j):
+                    continue
+                assert all((steps[i].off, steps[i].len) == (steps[ix[0]].off, steps[ix[0]].len) for i in ix), \
+                    f"tree {t} piece {j} chunk {c}: steps disagree on the range"
+                has = {j: -1}                      # rank -> step that delivered the chunk (-1: owner)
+                closure: Dict[int, set] = {}
+                for i in ix:
+                    s = steps[i]
+                    assert (s.src, s.dst) in edges, f"step {i} does not follow a tree edge"
+                    cl = set()
+                    for d in s.deps:
+                        cl |= {d} | closure.get(d, set())
+                    closure[i] = cl
+                    assert s.src in has, f"step {i} forwards a chunk rank {s.src} does not hold"
+                    assert has[s.src] == -1 or has[s.src] in cl, f"step {i} is not ordered after its input"
+                    assert s.dst not in has, f"rank {s.dst} receives piece {j} twice"
+                    has[s.dst] = i
+                if op == ALLGATHER:
+                    assert set(has) == set(range(k)), f"tree {t} piece {j} chunk {c}: not everywhere"
+                else:
+                    path = {j}
+                    v = j
+                    while parent[v] >= 0:
+                        v = parent[v]
+                        path.add(v)
+                    assert set(has) == path, f"tree {t} piece {j} chunk {c}: {sorted(has)} is not the path to the root"
 
 
 # --------------------------------------------------------------------------

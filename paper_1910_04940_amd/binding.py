@@ -21,7 +21,7 @@ BLINK_MAX_RANKS = 16
 BLINK_ROOT_ANY = -1
 BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP = range(6)
 BLINK_INT32, BLINK_FP32 = 0, 1
-BLINK_OP_BROADCAST, BLINK_OP_ALLREDUCE, BLINK_OP_REDUCE = 0, 1, 2
+BLINK_OP_BROADCAST, BLINK_OP_ALLREDUCE, BLINK_OP_REDUCE, BLINK_OP_ALLGATHER, BLINK_OP_GATHER = 0, 1, 2, 3, 4
 BLINK_SUM, BLINK_PROD, BLINK_MIN, BLINK_MAX = 0, 1, 2, 3
 BLINK_STEP_REDUCE, BLINK_STEP_COPY = 0, 1
 BLINK_FUSE_EDGE, BLINK_FUSE_NODE, BLINK_FUSE_TREE = 0, 1, 2
@@ -37,7 +37,7 @@ EXPORTS = [
     "blink_schedule_num_steps", "blink_schedule_num_stages", "blink_schedule_num_trees",
     "blink_schedule_get_steps", "blink_schedule_get_bounds", "blink_schedule_traffic_bytes",
     "blink_schedule_free", "blink_allreduce", "blink_broadcast", "blink_schedule_set_launch",
-    "blink_allreduce_op", "blink_reduce", "blink_strerror", "blink_miad_create", "blink_miad_chunk", "blink_miad_steady",
+    "blink_allreduce_op", "blink_reduce", "blink_allgather", "blink_gather", "blink_strerror", "blink_miad_create", "blink_miad_chunk", "blink_miad_steady",
     "blink_miad_report", "blink_miad_free",
 ]
 
@@ -109,7 +109,7 @@ def lib() -> C.CDLL:
     L.blink_schedule_traffic_bytes.restype = C.c_uint64
     L.blink_schedule_free.argtypes = [vp]
     L.blink_schedule_free.restype = None
-    for name in ("blink_allreduce", "blink_broadcast"):
+    for name in ("blink_allreduce", "blink_broadcast", "blink_allgather", "blink_gather"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, vp, vp]
     for name in ("blink_allreduce_op", "blink_reduce"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, C.c_int, vp, vp]
@@ -276,6 +276,18 @@ def blink_broadcast(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule
     arr = _pointers(bufs)
     _check(lib().blink_broadcast(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
            "blink_broadcast")
+
+
+def blink_allgather(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:
+    arr = _pointers(bufs)
+    _check(lib().blink_allgather(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
+           "blink_allgather")
+
+
+def blink_gather(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:
+    arr = _pointers(bufs)
+    _check(lib().blink_gather(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
+           "blink_gather")
 
 
 def blink_allreduce_op(bufs: Sequence, n_elems: int, dtype: int, redop: int, schedule: Schedule,

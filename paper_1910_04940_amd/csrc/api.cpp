@@ -160,6 +160,20 @@ blink_status_t blink_reduce(void* const* bufs, int k, size_t n_elems, blink_dtyp
     BLINK_GUARD_END
 }
 
+blink_status_t blink_allgather(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                               blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLGATHER, BLINK_SUM, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                            blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_GATHER, BLINK_SUM, stream);
+    BLINK_GUARD_END
+}
+
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems) {
     const bool tile_ok = tile_elems == 0 || (tile_elems >= 256 && tile_elems <= 65536 &&
                                              (tile_elems & (tile_elems - 1)) == 0);

@@ -533,7 +533,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tile_shift = tile_shift;
     p.redop = static_cast<unsigned>(redop);
     // Without dependencies the order of tiles is free: interleave the trees tile by tile.
-    p.group = s.has_deps ? 1u : static_cast<unsigned>(s.n_trees);
+    p.group = s.has_deps ? 1u : std::min(64u, std::max(1u, s.n_flows));
     hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), 0,
                        static_cast<hipStream_t>(stream), p);
     BLINK_HIP(hipGetLastError());

@@ -212,7 +212,7 @@ std::vector<StageTmpl> tree_stage(int k, int root, const ParentVec& parent, blin
         t.n_op = 1;
         t.op[0] = make_op(OP_LD, 0);
         for (int v = 0; v < k; ++v)
-            if (v != root) t.store_rank[t.n_store++] = static_cast<uint8_t>(v);
+            if (v != root && parent[v] >= 0) t.store_rank[t.n_store++] = static_cast<uint8_t>(v);
     }
     return {t};
 }
@@ -228,68 +228,113 @@ void finish_levels(std::vector<StageTmpl>& st) {
     }
 }
 
+// One tree carrying one contiguous range of the payload in one direction:
+// the unit the stage builders and the chunking work on.  AllReduce, Broadcast
+// and Reduce have one flow per tree (its share); AllGather and Gather have one
+// per tree and piece (the tree's share of that piece, moving away from, or
+// towards the root from, the piece's owner).
+struct Flow {
+    ParentVec parent;   // -1 at the flow's source, -2 for ranks that take no part
+    int root;
+    uint64_t lo, hi;    // element range
+    int tree;           // index of the packed tree it belongs to
+};
+
 struct Built {
     std::vector<StageTmpl> tmpl;
     std::vector<StageInst> inst;
     std::vector<std::pair<int, int>> where;  // per instance: (tree, chunk)
 };
 
-// Lay the stages of all trees and chunks out in execution order.  A stage of
+// Lay the stages of all flows and chunks out in execution order.  A stage of
 // level l on chunk c gets time slot c + l, the slot in which a fully pipelined
-// execution would run it; inside a slot the trees take turns (section 4.2.2:
+// execution would run it; inside a slot the flows take turns (section 4.2.2:
 // trees sharing the machine alternate chunk by chunk instead of one running
 // ahead).  Dependencies always sit in an earlier slot.
-Built instantiate(const std::vector<std::vector<StageTmpl>>& per_tree,
-                  const std::vector<uint64_t>& bounds, uint64_t chunk) {
+Built instantiate(const std::vector<std::vector<StageTmpl>>& per_flow, const std::vector<Flow>& flows,
+                  uint64_t chunk) {
     Built b;
     struct Key {
         uint64_t slot;
-        int tree, local;
+        int flow, local;
         uint64_t chunk_idx;
     };
     std::vector<Key> keys;
-    std::vector<size_t> tmpl_base(per_tree.size());
-    for (size_t t = 0; t < per_tree.size(); ++t) {
-        tmpl_base[t] = b.tmpl.size();
-        b.tmpl.insert(b.tmpl.end(), per_tree[t].begin(), per_tree[t].end());
-        const uint64_t share = bounds[t + 1] - bounds[t];
-        const uint64_t n_chunks = (share + chunk - 1) / chunk;
-        for (uint64_t c = 0; c < n_chunks; ++c)
-            for (size_t j = 0; j < per_tree[t].size(); ++j)
-                keys.push_back({c + per_tree[t][j].level, static_cast<int>(t), static_cast<int>(j), c});
+    std::vector<size_t> tmpl_base(per_flow.size());
+    std::vector<uint64_t> n_chunks(per_flow.size());
+    for (size_t f = 0; f < per_flow.size(); ++f) {
+        tmpl_base[f] = b.tmpl.size();
+        b.tmpl.insert(b.tmpl.end(), per_flow[f].begin(), per_flow[f].end());
+        n_chunks[f] = (flows[f].hi - flows[f].lo + chunk - 1) / chunk;
+        for (uint64_t c = 0; c < n_chunks[f]; ++c)
+            for (size_t j = 0; j < per_flow[f].size(); ++j)
+                keys.push_back({c + per_flow[f][j].level, static_cast<int>(f), static_cast<int>(j), c});
     }
     std::stable_sort(keys.begin(), keys.end(), [](const Key& a, const Key& b2) {
         if (a.slot != b2.slot) return a.slot < b2.slot;
         if (a.chunk_idx != b2.chunk_idx) return a.chunk_idx < b2.chunk_idx;  // older chunks first
-        if (a.tree != b2.tree) return a.tree < b2.tree;
+        if (a.flow != b2.flow) return a.flow < b2.flow;
         return a.local < b2.local;
     });
-    // position of (tree, chunk, local) in the order
-    std::vector<std::vector<int32_t>> pos(per_tree.size());
-    for (size_t t = 0; t < per_tree.size(); ++t) {
-        const uint64_t share = bounds[t + 1] - bounds[t];
-        pos[t].assign(((share + chunk - 1) / chunk) * per_tree[t].size(), -1);
-    }
+    // position of (flow, chunk, local) in the order
+    std::vector<std::vector<int32_t>> pos(per_flow.size());
+    for (size_t f = 0; f < per_flow.size(); ++f) pos[f].assign(n_chunks[f] * per_flow[f].size(), -1);
     for (size_t i = 0; i < keys.size(); ++i)
-        pos[keys[i].tree][keys[i].chunk_idx * per_tree[keys[i].tree].size() + keys[i].local] =
+        pos[keys[i].flow][keys[i].chunk_idx * per_flow[keys[i].flow].size() + keys[i].local] =
             static_cast<int32_t>(i);
     b.inst.resize(keys.size());
     b.where.resize(keys.size());
     for (size_t i = 0; i < keys.size(); ++i) {
         const Key& key = keys[i];
-        const StageTmpl& st = per_tree[key.tree][key.local];
+        const StageTmpl& st = per_flow[key.flow][key.local];
+        const Flow& fl = flows[key.flow];
         StageInst& in = b.inst[i];
-        in.off = bounds[key.tree] + key.chunk_idx * chunk;
-        in.len = static_cast<uint32_t>(std::min<uint64_t>(chunk, bounds[key.tree + 1] - in.off));
-        in.tmpl = static_cast<uint32_t>(tmpl_base[key.tree] + key.local);
+        in.off = fl.lo + key.chunk_idx * chunk;
+        in.len = static_cast<uint32_t>(std::min<uint64_t>(chunk, fl.hi - in.off));
+        in.tmpl = static_cast<uint32_t>(tmpl_base[key.flow] + key.local);
         in.pad = 0;
         in.n_dep = st.n_dep;
         for (int d = 0; d < kMaxDeps; ++d) in.dep[d] = -1;
         for (int d = 0; d < st.n_dep; ++d)
-            in.dep[d] = pos[key.tree][key.chunk_idx * per_tree[key.tree].size() + st.dep_local[d]];
-        b.where[i] = {key.tree, static_cast<int>(key.chunk_idx)};
+            in.dep[d] = pos[key.flow][key.chunk_idx * per_flow[key.flow].size() + st.dep_local[d]];
+        b.where[i] = {fl.tree, static_cast<int>(key.chunk_idx)};
     }
     return b;
+}
+
+// The same undirected tree with every edge directed away from new_root.
+ParentVec reroot(int k, const ParentVec& parent, int new_root) {
+    ParentVec out;
+    out.fill(-2);
+    out[new_root] = -1;
+    std::vector<int> stack{new_root};
+    while (!stack.empty()) {
+        const int u = stack.back();
+        stack.pop_back();
+        for (int v = 0; v < k; ++v) {
+            const bool linked = (parent[v] == u) || (parent[u] == v);
+            if (linked && out[v] == -2) {
+                out[v] = static_cast<int8_t>(u);
+                stack.push_back(v);
+            }
+        }
+    }
+    return out;
+}
+
+// Piece j climbing to the tree's root: j is the source, each ancestor receives
+// from the rank below it; nobody else takes part.  With `direct` the piece goes
+// to the root in one hop (what a fully fused pass does).
+ParentVec climb(const ParentVec& parent, int root, int j, bool direct) {
+    ParentVec out;
+    out.fill(-2);
+    out[j] = -1;
+    if (direct) {
+        if (root != j) out[root] = static_cast<int8_t>(j);
+        return out;
+    }
+    for (int v = j; parent[v] >= 0; v = parent[v]) out[parent[v]] = static_cast<int8_t>(v);
+    return out;
 }
 
 }  // namespace
@@ -336,30 +381,69 @@ blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint
                              blink_fusion_t fusion, Schedule& out) {
     const int T = trees.count(), k = trees.k;
     if (T < 1 || k < 2 || k > BLINK_MAX_RANKS || chunk == 0) return BLINK_EINVAL;
-    if (chunk > 0xFFFFFFFFull) chunk = 0xFFFFFFFFull - 3;  // a chunk is addressed with 32 bits
-    if (op != BLINK_OP_ALLREDUCE && op != BLINK_OP_BROADCAST && op != BLINK_OP_REDUCE) return BLINK_EINVAL;
+    if (chunk > 0xFFFFFFFCull) {  // a chunk is addressed with 32 bits
+        if (n > 0xFFFFFFFCull) return BLINK_EINVAL;
+        chunk = 0xFFFFFFFCull;    // no payload this small has a longer chunk
+    }
+    const bool gathers = op == BLINK_OP_ALLGATHER || op == BLINK_OP_GATHER;
+    if (op != BLINK_OP_ALLREDUCE && op != BLINK_OP_BROADCAST && op != BLINK_OP_REDUCE && !gathers)
+        return BLINK_EINVAL;
     if (fusion != BLINK_FUSE_EDGE && fusion != BLINK_FUSE_NODE && fusion != BLINK_FUSE_TREE)
         return BLINK_EINVAL;
     if (op == BLINK_OP_BROADCAST)
         for (int t = 1; t < T; ++t)
             if (trees.root[t] != trees.root[0]) return BLINK_EMISMATCH;
+    if (gathers && n % static_cast<uint64_t>(k) != 0) return BLINK_EINVAL;
     out.k = k;
     out.n_trees = T;
     out.op = op;
     out.fusion = fusion;
     out.n = n;
     out.chunk = chunk;
-    out.bounds = split_by_weight(n, trees.weight, 4);
+    // Gathers split every rank's piece (n/k elements) among the trees; the other
+    // collectives split the whole payload.
+    const uint64_t piece = gathers ? n / k : n;
+    out.bounds = split_by_weight(piece, trees.weight, 4);
 
-    std::vector<std::vector<StageTmpl>> edge(T), fused(T);
+    // Flows, and the collective each one is built as.  A piece spreading from its
+    // owner (AllGather) or climbing to the root (Gather) is a broadcast along a
+    // re-directed tree.
+    std::vector<Flow> flows, fused_flows;
+    const blink_op_t build_as = gathers ? BLINK_OP_BROADCAST : op;
     for (int t = 0; t < T; ++t) {
-        edge[t] = edge_stages(k, trees.root[t], trees.parent[t], op);
-        finish_levels(edge[t]);
-        if (fusion == BLINK_FUSE_NODE) fused[t] = node_stages(k, trees.root[t], trees.parent[t], op);
-        if (fusion == BLINK_FUSE_TREE) fused[t] = tree_stage(k, trees.root[t], trees.parent[t], op);
-        finish_levels(fused[t]);
+        if (!gathers) {
+            flows.push_back({trees.parent[t], trees.root[t], out.bounds[t], out.bounds[t + 1], t});
+            continue;
+        }
+        for (int j = 0; j < k; ++j) {
+            const uint64_t lo = static_cast<uint64_t>(j) * piece + out.bounds[t];
+            const uint64_t hi = static_cast<uint64_t>(j) * piece + out.bounds[t + 1];
+            if (op == BLINK_OP_ALLGATHER) {
+                flows.push_back({reroot(k, trees.parent[t], j), j, lo, hi, t});
+            } else if (j != trees.root[t]) {  // the root's own piece is already in place
+                flows.push_back({climb(trees.parent[t], trees.root[t], j, false), j, lo, hi, t});
+                fused_flows.push_back({climb(trees.parent[t], trees.root[t], j, true), j, lo, hi, t});
+            }
+        }
     }
-    Built e = instantiate(edge, out.bounds, chunk);
+    if (fused_flows.empty()) fused_flows = flows;
+    out.n_flows = static_cast<uint32_t>(fusion == BLINK_FUSE_TREE ? fused_flows.size() : flows.size());
+
+    std::vector<std::vector<StageTmpl>> edge(flows.size()), fused;
+    for (size_t f = 0; f < flows.size(); ++f) {
+        edge[f] = edge_stages(k, flows[f].root, flows[f].parent, build_as);
+        finish_levels(edge[f]);
+    }
+    const std::vector<Flow>& ff = fusion == BLINK_FUSE_TREE ? fused_flows : flows;
+    if (fusion != BLINK_FUSE_EDGE) {
+        fused.resize(ff.size());
+        for (size_t f = 0; f < ff.size(); ++f) {
+            fused[f] = fusion == BLINK_FUSE_NODE ? node_stages(k, ff[f].root, ff[f].parent, build_as)
+                                                 : tree_stage(k, ff[f].root, ff[f].parent, build_as);
+            finish_levels(fused[f]);
+        }
+    }
+    Built e = instantiate(edge, flows, chunk);
     out.steps.resize(e.inst.size());
     for (size_t i = 0; i < e.inst.size(); ++i) {
         const StageInst& in = e.inst[i];
@@ -380,7 +464,7 @@ blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint
         out.tmpl = std::move(e.tmpl);
         out.inst = std::move(e.inst);
     } else {
-        Built f = instantiate(fused, out.bounds, chunk);
+        Built f = instantiate(fused, ff, chunk);
         out.tmpl = std::move(f.tmpl);
         out.inst = std::move(f.inst);
     }

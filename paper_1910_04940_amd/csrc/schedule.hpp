@@ -44,6 +44,7 @@ static_assert(sizeof(StageTmpl) % 4 == 0, "StageTmpl is read as 32-bit words");
 struct Schedule {
     int k = 0;
     int n_trees = 0;
+    uint32_t n_flows = 0;                // (tree, range) pairs the stages were built for
     blink_op_t op = BLINK_OP_ALLREDUCE;
     blink_fusion_t fusion = BLINK_FUSE_EDGE;
     uint64_t n = 0, chunk = 0;

@@ -338,3 +338,50 @@ def test_reduce_to_the_roots(dev, top, root, fusion, redop):
     with pytest.raises(bl.BlinkError) as e:
         bl.blink_reduce(bufs, n, bl.BLINK_FP32, 9, sched, stream())
     assert e.value.status == bl.BLINK_EINVAL
+
+
+# ---- Gather and AllGather ---------------------------------------------------------------------
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.chain(5), 2),
+                                      (si.complete_graph(16), bl.BLINK_ROOT_ANY),
+                                      (si.induced(si.hybrid_cube_mesh(doubled=True), (0, 1, 3, 4, 5, 7)), 0)])
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_allgather_equals_concatenation(dev, top, root, fusion):
+    k = top.k
+    m, chunk = 20_003, 4096          # piece length not a multiple of 4: pieces start off 16-byte boundaries
+    n = k * m
+    trees = pack(top, root)
+    x = [si.payload(95, r, n, "int", "int32") for r in range(k)]
+    want = ox.allgather_definition(x)
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLGATHER, n, chunk, fusion)
+    bl.blink_allgather(bufs, n, bl.BLINK_INT32, sched, stream())
+    torch.cuda.synchronize()
+    for r, b in enumerate(bufs):
+        assert np.array_equal(b.cpu().numpy(), want), f"rank {r}"
+    # float payloads take the same path (bit copy, -0.0 and all)
+    xf = [si.payload(96, r, n, "normal", "fp32") for r in range(k)]
+    xf[1][m:2 * m:3] = -0.0
+    bufs = to_dev(xf, dev)
+    bl.blink_allgather(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    wantf = ox.allgather_definition(xf)
+    for b in bufs:
+        assert b.cpu().numpy().tobytes() == wantf.tobytes()
+
+
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 3), (si.star(6, 1), 1), (si.chain(4), 0)])
+@pytest.mark.parametrize("fusion", FUSIONS)
+def test_gather_collects_at_the_root(dev, top, root, fusion):
+    k = top.k
+    m, chunk = 16_384, 2048
+    n = k * m
+    trees = pack(top, root)
+    x = [si.payload(97, r, n, "uniform", "fp32") for r in range(k)]
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_GATHER, n, chunk, fusion)
+    bl.blink_gather(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    assert bufs[root].cpu().numpy().tobytes() == ox.allgather_definition(x).tobytes()
+    # nobody's own piece is disturbed
+    for r in range(k):
+        assert np.array_equal(bufs[r][r * m:(r + 1) * m].cpu().numpy(), x[r][r * m:(r + 1) * m])

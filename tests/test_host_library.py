@@ -227,3 +227,43 @@ def test_schedule_error_codes():
     assert e.value.status == bl.BLINK_EMISMATCH
     empty = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 0, 64)
     assert empty.num_steps == 0 and empty.num_stages == 0 and empty.traffic_bytes == 0
+
+
+# ---- Gather and AllGather -----------------------------------------------------------------
+GATHER_SCHED_CASES = [
+    (si.hybrid_cube_mesh(), 0, 8 * 10_001, 3000),
+    (si.complete_graph(4), 1, 4 * 4096, 1024),
+    (si.chain(6), 2, 6 * 500, 64),
+    (si.hybrid_cube_mesh(doubled=True), 5, 8 * 999, 1 << 20),
+]
+
+
+@pytest.mark.parametrize("top,root,n,chunk", GATHER_SCHED_CASES)
+@pytest.mark.parametrize("coll", [bl.BLINK_OP_ALLGATHER, bl.BLINK_OP_GATHER])
+@pytest.mark.parametrize("fusion", [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE])
+def test_gather_schedules_pass_oracle_validators(top, root, n, chunk, coll, fusion):
+    trees = pack(top, root)
+    roots, parents, w = trees.as_lists()
+    k = top.k
+    sched = bl.blink_make_schedule(trees, coll, n, chunk, fusion)
+    assert sched.bounds() == osch.split_by_weight(n // k, w)
+    steps = to_oracle_steps(sched)
+    ocoll = osch.ALLGATHER if coll == bl.BLINK_OP_ALLGATHER else osch.GATHER
+    osch.check_gather_steps(steps, k, roots, parents, w, ocoll, n, chunk)
+    assert len(steps) == len(osch.make_gather_steps(roots, parents, w, ocoll, n, chunk))
+    if coll == bl.BLINK_OP_ALLGATHER:
+        # every piece reaches the k-1 other ranks: per-edge it is read and written once per hop,
+        # fully fused it is read once and written k-1 times
+        per_piece = {bl.BLINK_FUSE_EDGE: 8 * (k - 1), bl.BLINK_FUSE_TREE: 4 * k}.get(fusion)
+        if per_piece:
+            assert sched.traffic_bytes == per_piece * n
+    elif fusion == bl.BLINK_FUSE_TREE:
+        # Gather fused: every piece but the root's goes to the root in one hop
+        assert sched.traffic_bytes == 8 * (n - n // k)
+
+
+def test_gather_needs_a_multiple_of_k():
+    trees = pack(si.complete_graph(4), 0)
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_make_schedule(trees, bl.BLINK_OP_ALLGATHER, 4 * 100 + 2, 64)
+    assert e.value.status == bl.BLINK_EINVAL

@@ -229,3 +229,40 @@ def test_reduce_to_root(top, root):
     leaves_everywhere = [v for v in range(top.k) if all(not og.children_of(t)[v] for t in trees)]
     for v in leaves_everywhere:
         assert bufs[v].tobytes() == x[v].tobytes()
+
+
+# ---- Gather and AllGather -------------------------------------------------------------------
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.chain(5), 2), (si.complete_graph(4), 1)])
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+def test_allgather_equals_concatenation_and_zero_padded_allreduce(top, root, dtype):
+    roots, trees, w = make(top, root)
+    k = top.k
+    m, chunk = 1003, 200
+    n = k * m
+    x = inputs(k, n, dtype, seed=14)
+    want = ox.allgather_definition(x)
+    bufs = [a.copy() for a in x]
+    steps = osch.make_gather_steps(roots, trees, w, osch.ALLGATHER, n, chunk)
+    ox.run_steps(bufs, steps, ox.random_topological_order(steps, 4))
+    for b in bufs:
+        assert b.tobytes() == want.tobytes()
+    # the paper's description: an AllReduce whose reduction has nothing to do
+    padded = []
+    for j in range(k):
+        z = np.zeros(n, x[0].dtype)
+        z[j * m:(j + 1) * m] = x[j][j * m:(j + 1) * m]
+        padded.append(z)
+    ox.run_steps(padded, osch.make_steps(roots, trees, w, osch.ALLREDUCE, n, chunk))
+    assert np.array_equal(padded[0], want)          # values (a stored -0.0 would come back as +0.0)
+
+
+@pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 3), (si.star(5, 2), 2)])
+def test_gather_collects_at_the_root(top, root):
+    roots, trees, w = make(top, root)
+    k = top.k
+    n, chunk = k * 500, 64
+    x = inputs(k, n, "fp32", seed=15)
+    bufs = [a.copy() for a in x]
+    steps = osch.make_gather_steps(roots, trees, w, osch.GATHER, n, chunk)
+    ox.run_steps(bufs, steps, ox.random_topological_order(steps, 5))
+    assert bufs[root].tobytes() == ox.allgather_definition(x).tobytes()

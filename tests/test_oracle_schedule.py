@@ -173,3 +173,70 @@ def test_chain_makespan_is_hops_plus_chunks_minus_one(hops, chunks):
     assert osch.pipeline_makespan(steps) == hops + chunks - 1
     steps = osch.make_steps([0], [parent], [1.0], osch.ALLREDUCE, 64 * chunks, 64)
     assert osch.pipeline_makespan(steps) == 2 * hops + chunks - 1
+
+
+# ---- Gather and AllGather (section 4.1) -----------------------------------------------------
+def test_reroot_and_climb():
+    parent = (-1, 0, 0, 2, 2)            # 0 -> {1, 2}, 2 -> {3, 4}
+    assert osch.reroot(parent, 0) == parent
+    assert osch.reroot(parent, 3) == (2, 0, 3, -1, 2)
+    assert osch.reroot(osch.reroot(parent, 4), 0) == parent
+    assert osch.climb(parent, 3) == (2, -2, 3, -1, -2)
+    assert osch.climb(parent, 0) == (-1, -2, -2, -2, -2)
+
+
+GATHER_CASES = [(si.hybrid_cube_mesh(), 0, 8 * 1001, 300), (si.complete_graph(4), 2, 4 * 64, 64),
+                (si.chain(5), 1, 5 * 777, 100), (si.star(6, 0), 0, 6 * 10, 4)]
+
+
+@pytest.mark.parametrize("top,root,n,chunk", GATHER_CASES)
+def test_allgather_steps(top, root, n, chunk):
+    roots, trees, w = trees_for(top, root)
+    k = top.k
+    steps = osch.make_gather_steps(roots, trees, w, osch.ALLGATHER, n, chunk)
+    osch.check_gather_steps(steps, k, roots, trees, w, osch.ALLGATHER, n, chunk)
+    # every rank other than the owner receives every piece once: k(k-1) copies per tree and chunk position
+    m = n // k
+    b = osch.split_by_weight(m, w)
+    per_piece_chunks = sum(len(osch.chunk_ranges(b[t], b[t + 1], chunk)) for t in range(len(trees)))
+    assert len(steps) == k * (k - 1) * per_piece_chunks
+    # "AllReduce without a reduction": the directed edges in use are the tree's edges in both directions
+    for t, (r, parent) in enumerate(zip(roots, trees)):
+        used = {(s.src, s.dst) for s in steps if s.tree == t}
+        arcs = {(parent[v], v) for v in range(k) if v != r}
+        assert used == arcs | {(b_, a) for (a, b_) in arcs}
+
+
+@pytest.mark.parametrize("top,root,n,chunk", GATHER_CASES)
+def test_gather_is_the_inverse_of_broadcast(top, root, n, chunk):
+    roots, trees, w = trees_for(top, root)
+    k = top.k
+    steps = osch.make_gather_steps(roots, trees, w, osch.GATHER, n, chunk)
+    osch.check_gather_steps(steps, k, roots, trees, w, osch.GATHER, n, chunk)
+    bc = osch.make_steps(roots, trees, w, osch.BROADCAST, n // k, chunk)
+    for t in range(len(trees)):
+        assert {(s.dst, s.src) for s in steps if s.tree == t} == {(s.src, s.dst) for s in bc if s.tree == t}
+    # piece j makes depth(j) hops
+    for t, (r, parent) in enumerate(zip(roots, trees)):
+        for j in range(k):
+            depth, v = 0, j
+            while parent[v] >= 0:
+                v, depth = parent[v], depth + 1
+            hops = {(s.src, s.dst) for s in steps if s.tree == t and s.off // (n // k) == j}
+            assert len(hops) == depth
+
+
+def test_gather_validators_catch_planted_mistakes():
+    top = si.hybrid_cube_mesh()
+    roots, trees, w = trees_for(top, 0)
+    n, c = 8 * 512, 128
+    steps = osch.make_gather_steps(roots, trees, w, osch.ALLGATHER, n, c)
+    args = (8, roots, trees, w, osch.ALLGATHER, n, c)
+    osch.check_gather_steps(steps, *args)
+    i = next(i for i, s in enumerate(steps) if s.deps)
+    for bad in (_mutate(steps, i, deps=()), _mutate(steps, i, src=steps[i].dst, dst=steps[i].src),
+                _mutate(steps, i, off=steps[i].off + 4), steps[:-1], _mutate(steps, i, kind=osch.REDUCE)):
+        with pytest.raises(AssertionError):
+            osch.check_gather_steps(bad, *args)
+    with pytest.raises(ValueError):
+        osch.make_gather_steps(roots, trees, w, osch.ALLGATHER, 8 * 512 + 1, c)
