@@ -96,6 +96,53 @@ def hybrid_cube_mesh(doubled: bool = False) -> Topology:
                        "cube_mesh_doubled" if doubled else "cube_mesh")
 
 
+def dgx1v() -> Topology:
+    """The 8-GPU second-generation server with its actual link multiplicities:
+    the hybrid cube-mesh's 16 links, eight of them doubled (0-3, 0-4, 1-2, 1-5,
+    2-3, 4-7, 5-6, 6-7), six link-units per GPU.  The paper's text does not list
+    which links are doubled (its figure is not available); this assignment
+    reproduces the paper's count of 46 distinct connected 3- to 8-GPU
+    allocations, which ``hybrid_cube_mesh(doubled=True)`` (22) does not."""
+    two = [(0, 3), (0, 4), (1, 2), (1, 5), (2, 3), (4, 7), (5, 6), (6, 7)]
+    one = [(0, 1), (0, 2), (1, 3), (2, 6), (3, 7), (4, 5), (4, 6), (5, 7)]
+    return _from_links(8, [(a, b, 2.0) for a, b in two] + [(a, b, 1.0) for a, b in one], "dgx1v")
+
+
+def connected_allocations(top: Topology, sizes: Sequence[int] = (3, 4, 5, 6, 7, 8)) -> List[Tuple[int, ...]]:
+    """All vertex subsets of the given sizes whose induced sub-topology is connected."""
+    import itertools
+    linked = {(int(u), int(v)) for u, v in zip(top.src, top.dst)}
+    out = []
+    for size in sizes:
+        for sub in itertools.combinations(range(top.k), size):
+            seen, stack = {sub[0]}, [sub[0]]
+            while stack:
+                x = stack.pop()
+                for y in sub:
+                    if y not in seen and (x, y) in linked:
+                        seen.add(y)
+                        stack.append(y)
+            if len(seen) == size:
+                out.append(sub)
+    return out
+
+
+def count_distinct_allocations(top: Topology, subsets: Sequence[Tuple[int, ...]]) -> int:
+    """Number of subsets up to relabelling (same links with the same capacities):
+    smallest capacity matrix over all vertex orders (brute force, <= 8 vertices)."""
+    import itertools
+    cap = {(int(u), int(v)): float(c) for u, v, c in zip(top.src, top.dst, top.cap)}
+    forms = set()
+    for sub in subsets:
+        best = None
+        for perm in itertools.permutations(sub):
+            key = tuple(cap.get((perm[i], perm[j]), 0.0) for i in range(len(sub)) for j in range(i + 1, len(sub)))
+            if best is None or key < best:
+                best = key
+        forms.add((len(sub), best))
+    return len(forms)
+
+
 def induced(top: Topology, ranks: Sequence[int]) -> Topology:
     """Sub-topology on ``ranks`` (a fragmented allocation); vertices renumbered
     0..len(ranks)-1 in the order given."""
