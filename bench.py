@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--chunk-bytes", type=int, default=1 << 20)
     ap.add_argument("--elems", type=int, default=1 << 26, help="fp32 elements per rank")
     ap.add_argument("--dtype", choices=["fp32", "int32"], default="fp32")
-    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--tile-elems", type=int, default=0,
+                    help="elements per ticket (power of two in 256..65536; 0 = library default)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="verify sampled outputs against the oracle")
@@ -129,8 +130,8 @@ def main():
     trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
     roots, parents, weights = trees.as_lists()
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
-    if args.unroll or args.wg_per_cu:
-        sched.set_launch(args.wg_per_cu, args.unroll)
+    if args.tile_elems or args.wg_per_cu:
+        sched.set_launch(args.wg_per_cu, args.tile_elems)
 
     # inputs: uniform[-1,1] (or full-range int32), generated on the host from the
     # shared seeded recipe, resident in HBM before anything is timed
