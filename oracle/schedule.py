@@ -30,7 +30,7 @@ from __future__ import annotations
 import math
 from dataclasses import dataclass
 from fractions import Fraction
-from typing import Dict, List, Sequence, Tuple
+from typing import Dict, List, Optional, Sequence, Tuple
 
 from .graph import children_of
 
@@ -79,11 +79,11 @@ def chunk_ranges(lo: int, hi: int, chunk: int) -> List[Tuple[int, int]]:
     return [(o, min(chunk, hi - o)) for o in range(lo, hi, chunk)]
 
 
-def reduce_order(root: int, parent: Sequence[int]) -> List[int]:
+def reduce_order(root: int, parent: Sequence[int], ch: Optional[List[List[int]]] = None) -> List[int]:
     """Non-root vertices, every vertex after all vertices of its subtree
-    (post-order, children ascending): the order of the child->parent
-    transfers of the reduce phase."""
-    ch = children_of(parent)
+    (post-order, children ascending unless ``ch`` gives another order): the
+    order of the child->parent transfers of the reduce phase."""
+    ch = children_of(parent) if ch is None else ch
     out: List[int] = []
 
     def visit(v: int) -> None:
@@ -96,10 +96,11 @@ def reduce_order(root: int, parent: Sequence[int]) -> List[int]:
     return out
 
 
-def broadcast_order(root: int, parent: Sequence[int]) -> List[int]:
+def broadcast_order(root: int, parent: Sequence[int], ch: Optional[List[List[int]]] = None) -> List[int]:
     """Non-root vertices in breadth-first order from the root (children
-    ascending): the order of the parent->child transfers."""
-    ch = children_of(parent)
+    ascending unless ``ch`` gives another order): the order of the
+    parent->child transfers."""
+    ch = children_of(parent) if ch is None else ch
     out: List[int] = []
     frontier = [root]
     while frontier:
@@ -125,32 +126,38 @@ def make_steps(roots: Sequence[int], trees: Sequence[Sequence[int]],
     bounds = split_by_weight(n, weights)
     steps: List[Step] = []
     for t, (root, parent) in enumerate(zip(roots, trees)):
-        ch = children_of(parent)
-        for c, (off, ln) in enumerate(chunk_ranges(bounds[t], bounds[t + 1], chunk)):
-            red: Dict[int, int] = {}   # vertex -> index of its REDUCE-out step
-            cp: Dict[int, int] = {}    # vertex -> index of the COPY into it
-            if op in (ALLREDUCE, REDUCE_TO_ROOT):
-                for v in reduce_order(root, parent):
-                    p = parent[v]
-                    deps = []
-                    if ch[v]:
-                        deps.append(red[ch[v][-1]])
-                    i = ch[p].index(v)
-                    if i > 0:
-                        deps.append(red[ch[p][i - 1]])
-                    red[v] = len(steps)
-                    steps.append(Step(REDUCE, t, c, v, p, off, ln, tuple(deps)))
-            for v in (broadcast_order(root, parent) if op != REDUCE_TO_ROOT else []):
-                p = parent[v]
-                if p != root:
-                    deps = (cp[p],)
-                elif op == ALLREDUCE:
-                    deps = (red[ch[root][-1]],)
-                else:
-                    deps = ()
-                cp[v] = len(steps)
-                steps.append(Step(COPY, t, c, p, v, off, ln, deps))
+        emit_tree_steps(steps, t, root, parent, children_of(parent), op, bounds[t], bounds[t + 1], chunk)
     return steps
+
+
+def emit_tree_steps(steps: List[Step], t: int, root: int, parent: Sequence[int],
+                    ch: List[List[int]], op: int, lo: int, hi: int, chunk: int) -> None:
+    """Append the steps of one tree on the range [lo, hi), chunk by chunk.  ``ch``
+    lists every vertex's children in the order they are folded in."""
+    for c, (off, ln) in enumerate(chunk_ranges(lo, hi, chunk)):
+        red: Dict[int, int] = {}   # vertex -> index of its REDUCE-out step
+        cp: Dict[int, int] = {}    # vertex -> index of the COPY into it
+        if op in (ALLREDUCE, REDUCE_TO_ROOT):
+            for v in reduce_order(root, parent, ch):
+                p = parent[v]
+                deps = []
+                if ch[v]:
+                    deps.append(red[ch[v][-1]])
+                i = ch[p].index(v)
+                if i > 0:
+                    deps.append(red[ch[p][i - 1]])
+                red[v] = len(steps)
+                steps.append(Step(REDUCE, t, c, v, p, off, ln, tuple(deps)))
+        for v in (broadcast_order(root, parent, ch) if op != REDUCE_TO_ROOT else []):
+            p = parent[v]
+            if p != root:
+                deps = (cp[p],)
+            elif op == ALLREDUCE:
+                deps = (red[ch[root][-1]],)
+            else:
+                deps = ()
+            cp[v] = len(steps)
+            steps.append(Step(COPY, t, c, p, v, off, ln, deps))
 
 
 # --------------------------------------------------------------------------
@@ -344,12 +351,13 @@ def _tree_order_expr(v: int, ch: List[List[int]]):
     return e
 
 
-def _symbolic_replay(steps, idx, k, root, parent, op) -> None:
+def _symbolic_replay(steps, idx, k, root, parent, op, ch=None) -> None:
     """Run one (tree, chunk)'s steps on symbolic values.  Each rank's cell holds
     (expression, index of the step that wrote it or -1).  A step may only read a
     cell whose writer is among its transitive dependencies, and may only
-    overwrite a cell whose earlier readers are among them too."""
-    ch = children_of(parent)
+    overwrite a cell whose earlier readers are among them too.  ``ch``: the
+    children in folding order when that is not ascending id."""
+    ch = children_of(parent) if ch is None else ch
     val = [(("x", v), -1) for v in range(k)]
     readers: List[List[int]] = [[] for _ in range(k)]
     closure: Dict[int, set] = {}
