@@ -13,6 +13,8 @@
  *   blink_allreduce      on a HIP stream (paper sections 3.3, 4.1)
  *   blink_miad_*         pick the chunk size over the first iterations of a job
  *                        (paper section 4.2.1)
+ *   blink_make_schedule_servers / blink_hybrid_split
+ *                        several servers, two classes of links (sections 3.5, 3.4)
  *
  * Conventions
  *   - Every function that can fail returns blink_status_t; results come back
@@ -158,6 +160,40 @@ void blink_trees_free(blink_trees_t* trees);
 blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, size_t n_elems,
                                    size_t chunk_elems, blink_fusion_t fusion,
                                    blink_schedule_t** out);
+
+/* AllReduce across n_servers servers, each with its own packed local trees
+ * (section 3.5, the three-phase protocol): inside every server the root of a
+ * tree reduces its partition of the payload over that tree; the server-local
+ * roots of a partition then run a one-hop reduce-broadcast among themselves,
+ * each of them owning one n-th of the partition; every root finally broadcasts
+ * over its local tree.
+ *   local[n_servers] (host): each server's trees; null for a server with one rank.
+ *   ranks (host): for server 0, 1, .. in turn, the global rank id of each of its
+ *       local ranks, strictly ascending inside a server; together a permutation
+ *       of 0 .. k-1, k = total number of ranks <= BLINK_MAX_RANKS.
+ * Partitions are the common refinement of the servers' weighted splits, so
+ * that one tree per server serves a partition; the i-th smallest root id owns
+ * the i-th of the n equal pieces (4-element alignment) of a partition and adds
+ * the other roots' partial sums in ascending id after its own local sum.
+ * The result is a schedule for BLINK_OP_ALLREDUCE on k ranks (run it with
+ * blink_allreduce / blink_allreduce_op); its "trees" are the (partition,
+ * piece) pairs with non-empty range, in payload order.  The local handles are
+ * not retained. */
+blink_status_t blink_make_schedule_servers(int n_servers, const blink_trees_t* const* local,
+                                           const int32_t* ranks, size_t n_elems,
+                                           size_t chunk_elems, blink_fusion_t fusion,
+                                           blink_schedule_t** out);
+
+/* Split of d_total between a slow and a fast class of links (section 3.4, the
+ * PCIe / NVLink case) so that both finish together when the slow class first
+ * pays the switch-over latency t_switch:
+ *   d_slow / bw_slow + t_switch = d_fast / bw_fast,  d_slow + d_fast = d_total.
+ * d_slow is clamped to [0, d_total] (nothing goes over the slow class when the
+ * latency outweighs it).  Units are the caller's (bytes, bytes/s, s).
+ * BLINK_EINVAL for non-positive bandwidths, negative sizes or latencies, or
+ * null outputs. */
+blink_status_t blink_hybrid_split(double d_total, double bw_slow, double bw_fast, double t_switch,
+                                  double* d_slow, double* d_fast);
 
 size_t blink_schedule_num_steps(const blink_schedule_t* s);   /* tree-edge transfers */
 size_t blink_schedule_num_stages(const blink_schedule_t* s);  /* passes the kernel makes (== steps for EDGE) */

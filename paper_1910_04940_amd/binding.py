@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes as C
 import importlib.util
 import os
-from typing import List, Sequence, Tuple
+from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -37,8 +37,9 @@ EXPORTS = [
     "blink_schedule_num_steps", "blink_schedule_num_stages", "blink_schedule_num_trees",
     "blink_schedule_get_steps", "blink_schedule_get_bounds", "blink_schedule_traffic_bytes",
     "blink_schedule_free", "blink_allreduce", "blink_broadcast", "blink_schedule_set_launch",
-    "blink_allreduce_op", "blink_reduce", "blink_allgather", "blink_gather", "blink_strerror", "blink_miad_create", "blink_miad_chunk", "blink_miad_steady",
-    "blink_miad_report", "blink_miad_free",
+    "blink_allreduce_op", "blink_reduce", "blink_allgather", "blink_gather", "blink_strerror",
+    "blink_miad_create", "blink_miad_chunk", "blink_miad_steady", "blink_miad_report",
+    "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
 ]
 
 
@@ -98,6 +99,9 @@ def lib() -> C.CDLL:
     L.blink_trees_free.argtypes = [vp]
     L.blink_trees_free.restype = None
     L.blink_make_schedule.argtypes = [vp, C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.POINTER(vp)]
+    L.blink_make_schedule_servers.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(C.c_int32), C.c_size_t,
+                                              C.c_size_t, C.c_int, C.POINTER(vp)]
+    L.blink_hybrid_split.argtypes = [C.c_double] * 4 + [C.POINTER(C.c_double)] * 2
     L.blink_schedule_num_steps.argtypes = [vp]
     L.blink_schedule_num_steps.restype = C.c_size_t
     L.blink_schedule_num_stages.argtypes = [vp]
@@ -258,6 +262,32 @@ def blink_make_schedule(trees: Trees, op: int, n_elems: int, chunk_elems: int,
     _check(lib().blink_make_schedule(trees._h, op, n_elems, chunk_elems, fusion, C.byref(out)),
            "blink_make_schedule")
     return Schedule(out.value, trees.k, n_elems, op)
+
+
+def blink_make_schedule_servers(local: Sequence[Optional[Trees]], ranks: Sequence[Sequence[int]],
+                                n_elems: int, chunk_elems: int,
+                                fusion: int = BLINK_FUSE_TREE) -> Schedule:
+    """local[s]: server s's trees (None for a one-rank server); ranks[s]: the
+    global ids of its local ranks, ascending."""
+    if len(local) != len(ranks):
+        raise ValueError("one rank list per server")
+    for t, r in zip(local, ranks):
+        if len(r) != (t.k if t is not None else 1):
+            raise ValueError("a server's rank list must have one id per local rank")
+    handles = (C.c_void_p * len(local))(*[t._h if t is not None else None for t in local])
+    flat = np.ascontiguousarray([g for r in ranks for g in r], dtype=np.int32)
+    out = C.c_void_p()
+    _check(lib().blink_make_schedule_servers(len(local), handles, _ptr(flat, C.c_int32), n_elems,
+                                             chunk_elems, fusion, C.byref(out)),
+           "blink_make_schedule_servers")
+    return Schedule(out.value, len(flat), n_elems, BLINK_OP_ALLREDUCE)
+
+
+def blink_hybrid_split(d_total: float, bw_slow: float, bw_fast: float, t_switch: float):
+    a, b = C.c_double(), C.c_double()
+    _check(lib().blink_hybrid_split(d_total, bw_slow, bw_fast, t_switch, C.byref(a), C.byref(b)),
+           "blink_hybrid_split")
+    return a.value, b.value
 
 
 def _pointers(bufs: Sequence) -> "C.Array":

@@ -108,6 +108,50 @@ blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, si
     BLINK_GUARD_END
 }
 
+blink_status_t blink_make_schedule_servers(int n_servers, const blink_trees_t* const* local,
+                                           const int32_t* ranks, size_t n_elems,
+                                           size_t chunk_elems, blink_fusion_t fusion,
+                                           blink_schedule_t** out) {
+    if (!out) return BLINK_EINVAL;
+    *out = nullptr;
+    if (n_servers < 1 || n_servers > BLINK_MAX_RANKS || !local || !ranks) return BLINK_EINVAL;
+    BLINK_GUARD_BEGIN
+    std::vector<blink::ServerTrees> servers(n_servers);
+    size_t at = 0;
+    for (int s = 0; s < n_servers; ++s) {
+        servers[s].trees = local[s] ? &local[s]->t : nullptr;
+        const size_t ks = local[s] ? static_cast<size_t>(local[s]->t.k) : 1;
+        if (at + ks > BLINK_MAX_RANKS) return BLINK_EINVAL;
+        servers[s].ranks.assign(ranks + at, ranks + at + ks);
+        at += ks;
+    }
+    blink_schedule_t* h = new blink_schedule_t();
+    const blink_status_t st = blink::make_schedule_servers(servers, n_elems, chunk_elems, fusion, h->s);
+    if (st != BLINK_OK) {
+        delete h;
+        return st;
+    }
+    *out = h;
+    return BLINK_OK;
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_hybrid_split(double d_total, double bw_slow, double bw_fast, double t_switch,
+                                  double* d_slow, double* d_fast) {
+    if (!d_slow || !d_fast) return BLINK_EINVAL;
+    if (!(bw_slow > 0) || !(bw_fast > 0) || !(d_total >= 0) || !(t_switch >= 0)) return BLINK_EINVAL;
+    if (!std::isfinite(d_total) || !std::isfinite(bw_slow) || !std::isfinite(bw_fast) ||
+        !std::isfinite(t_switch))
+        return BLINK_EINVAL;
+    // Equal finishing times: d_slow/bw_slow + t_switch = (d_total - d_slow)/bw_fast.
+    const double sum = bw_slow + bw_fast;
+    double slow = d_total * (bw_slow / sum) - t_switch * (bw_slow / sum) * bw_fast;
+    slow = slow < 0 ? 0 : (slow > d_total ? d_total : slow);
+    *d_slow = slow;
+    *d_fast = d_total - slow;
+    return BLINK_OK;
+}
+
 size_t blink_schedule_num_steps(const blink_schedule_t* s) { return s ? s->s.steps.size() : 0; }
 size_t blink_schedule_num_stages(const blink_schedule_t* s) { return s ? s->s.inst.size() : 0; }
 int blink_schedule_num_trees(const blink_schedule_t* s) { return s ? s->s.n_trees : -1; }

@@ -64,11 +64,23 @@ StageTmpl blank() {
     return t;
 }
 
+// Children in the order they are folded in: ascending id, except that the
+// vertices in the bit set `late` (attached to their parent by a later phase of
+// a multi-server protocol, section 3.5) come after all others.
+std::vector<std::vector<int>> ordered_children(int k, const ParentVec& parent, uint16_t late) {
+    auto ch = children(k, parent);
+    if (late)
+        for (auto& cs : ch)
+            std::stable_partition(cs.begin(), cs.end(), [late](int c) { return !((late >> c) & 1); });
+    return ch;
+}
+
 // One stage per tree-edge transfer, in the paper's order: reduce phase child ->
 // parent with every vertex after its whole subtree, then copy phase parent ->
 // child breadth first.
-std::vector<StageTmpl> edge_stages(int k, int root, const ParentVec& parent, blink_op_t op) {
-    const auto ch = children(k, parent);
+std::vector<StageTmpl> edge_stages(int k, int root, const ParentVec& parent, uint16_t late,
+                                   blink_op_t op) {
+    const auto ch = ordered_children(k, parent, late);
     std::vector<StageTmpl> out;
     std::vector<int> red(k, -1), cp(k, -1);
     if (op != BLINK_OP_BROADCAST) {
@@ -120,10 +132,11 @@ std::vector<StageTmpl> edge_stages(int k, int root, const ParentVec& parent, bli
     return out;
 }
 
-// One stage per fan-in (a node folds itself and all its children, ascending)
-// and one per fan-out; the root's fan-in also writes the result to its children.
-std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, blink_op_t op) {
-    const auto ch = children(k, parent);
+// One stage per fan-in (a node folds itself and all its children, in folding
+// order) and one per fan-out; the root's fan-in also writes the result to its children.
+std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, uint16_t late,
+                                   blink_op_t op) {
+    const auto ch = ordered_children(k, parent, late);
     std::vector<StageTmpl> out;
     std::vector<int> fin(k, -1), fout(k, -1);
     if (op != BLINK_OP_BROADCAST) {
@@ -171,7 +184,7 @@ std::vector<StageTmpl> node_stages(int k, int root, const ParentVec& parent, bli
     return out;
 }
 
-// acc <- S(v) = ((x_v + S(c_1)) + S(c_2)) + ..., children ascending.  Slot i
+// acc <- S(v) = ((x_v + S(c_1)) + S(c_2)) + ..., children in folding order.  Slot i
 // holds x_i.  The first child's sum is formed first and x_v added to it (IEEE
 // addition and multiplication commute bit for bit, and min/max are taken under
 // a total order, so the bits equal x_v (+) S(c_1)); before a later child
@@ -197,11 +210,12 @@ void eval_tree(int v, const std::vector<std::vector<int>>& ch, StageTmpl& t) {
 }
 
 // The whole tree in one stage: every rank read once and written once.
-std::vector<StageTmpl> tree_stage(int k, int root, const ParentVec& parent, blink_op_t op) {
+std::vector<StageTmpl> tree_stage(int k, int root, const ParentVec& parent, uint16_t late,
+                                  blink_op_t op) {
     StageTmpl t = blank();
     if (op != BLINK_OP_BROADCAST) {
         for (int v = 0; v < k; ++v) t.load_rank[t.n_load++] = static_cast<uint8_t>(v);
-        eval_tree(root, children(k, parent), t);
+        eval_tree(root, ordered_children(k, parent, late), t);
         if (op == BLINK_OP_REDUCE)
             t.store_rank[t.n_store++] = static_cast<uint8_t>(root);
         else
@@ -238,6 +252,7 @@ struct Flow {
     int root;
     uint64_t lo, hi;    // element range
     int tree;           // index of the packed tree it belongs to
+    uint16_t late = 0;  // bit set of vertices folded in after their siblings (see ordered_children)
 };
 
 struct Built {
@@ -337,6 +352,69 @@ ParentVec climb(const ParentVec& parent, int root, int j, bool direct) {
     return out;
 }
 
+// Stages, instances, the public step list and the totals of a schedule whose
+// flows are known.  `fused_flows`: what a fully fused pass works on when that
+// differs from the tree-edge flows (empty = the same).
+void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink_op_t build_as,
+            Schedule& out) {
+    const int k = out.k;
+    const uint64_t chunk = out.chunk;
+    const blink_fusion_t fusion = out.fusion;
+    if (fused_flows.empty()) fused_flows = flows;
+    out.n_flows = static_cast<uint32_t>(fusion == BLINK_FUSE_TREE ? fused_flows.size() : flows.size());
+
+    std::vector<std::vector<StageTmpl>> edge(flows.size()), fused;
+    for (size_t f = 0; f < flows.size(); ++f) {
+        edge[f] = edge_stages(k, flows[f].root, flows[f].parent, flows[f].late, build_as);
+        finish_levels(edge[f]);
+    }
+    const std::vector<Flow>& ff = fusion == BLINK_FUSE_TREE ? fused_flows : flows;
+    if (fusion != BLINK_FUSE_EDGE) {
+        fused.resize(ff.size());
+        for (size_t f = 0; f < ff.size(); ++f) {
+            fused[f] = fusion == BLINK_FUSE_NODE ? node_stages(k, ff[f].root, ff[f].parent, ff[f].late, build_as)
+                                                 : tree_stage(k, ff[f].root, ff[f].parent, ff[f].late, build_as);
+            finish_levels(fused[f]);
+        }
+    }
+    Built e = instantiate(edge, flows, chunk);
+    out.steps.resize(e.inst.size());
+    for (size_t i = 0; i < e.inst.size(); ++i) {
+        const StageInst& in = e.inst[i];
+        const StageTmpl& st = e.tmpl[in.tmpl];
+        blink_step_t& s = out.steps[i];
+        s.kind = st.n_load == 2 ? BLINK_STEP_REDUCE : BLINK_STEP_COPY;
+        s.tree = e.where[i].first;
+        s.chunk = e.where[i].second;
+        s.src = st.n_load == 2 ? st.load_rank[1] : st.load_rank[0];
+        s.dst = st.store_rank[0];
+        s.n_deps = in.n_dep;
+        s.deps[0] = in.n_dep > 0 ? in.dep[0] : -1;
+        s.deps[1] = in.n_dep > 1 ? in.dep[1] : -1;
+        s.off = in.off;
+        s.len = in.len;
+    }
+    if (fusion == BLINK_FUSE_EDGE) {
+        out.tmpl = std::move(e.tmpl);
+        out.inst = std::move(e.inst);
+    } else {
+        Built f = instantiate(fused, ff, chunk);
+        out.tmpl = std::move(f.tmpl);
+        out.inst = std::move(f.inst);
+    }
+    out.max_slots = 1;
+    out.traffic_bytes = 0;
+    out.has_deps = false;
+    for (const StageTmpl& st : out.tmpl) {
+        out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
+        out.has_deps = out.has_deps || st.n_dep > 0;
+    }
+    for (const StageInst& in : out.inst) {
+        const StageTmpl& st = out.tmpl[in.tmpl];
+        out.traffic_bytes += static_cast<uint64_t>(in.len) * 4u * (st.n_load + st.n_store);
+    }
+}
+
 }  // namespace
 
 std::vector<uint64_t> split_by_weight(uint64_t n, const std::vector<double>& w, uint64_t align) {
@@ -426,59 +504,102 @@ blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint
             }
         }
     }
-    if (fused_flows.empty()) fused_flows = flows;
-    out.n_flows = static_cast<uint32_t>(fusion == BLINK_FUSE_TREE ? fused_flows.size() : flows.size());
+    finish(flows, fused_flows, build_as, out);
+    return BLINK_OK;
+}
 
-    std::vector<std::vector<StageTmpl>> edge(flows.size()), fused;
-    for (size_t f = 0; f < flows.size(); ++f) {
-        edge[f] = edge_stages(k, flows[f].root, flows[f].parent, build_as);
-        finish_levels(edge[f]);
+// Section 3.5.  The three phases of one (partition, piece) amount to an
+// AllReduce along one global tree: the piece's owner (a server-local root) with
+// its local tree below it and the other servers' local trees hanging off it
+// through their roots, those roots folded in after the owner's local children.
+blink_status_t make_schedule_servers(const std::vector<ServerTrees>& servers, uint64_t n,
+                                     uint64_t chunk, blink_fusion_t fusion, Schedule& out) {
+    const size_t S = servers.size();
+    if (S < 1 || chunk == 0) return BLINK_EINVAL;
+    if (fusion != BLINK_FUSE_EDGE && fusion != BLINK_FUSE_NODE && fusion != BLINK_FUSE_TREE)
+        return BLINK_EINVAL;
+    if (chunk > 0xFFFFFFFCull) {
+        if (n > 0xFFFFFFFCull) return BLINK_EINVAL;
+        chunk = 0xFFFFFFFCull;
     }
-    const std::vector<Flow>& ff = fusion == BLINK_FUSE_TREE ? fused_flows : flows;
-    if (fusion != BLINK_FUSE_EDGE) {
-        fused.resize(ff.size());
-        for (size_t f = 0; f < ff.size(); ++f) {
-            fused[f] = fusion == BLINK_FUSE_NODE ? node_stages(k, ff[f].root, ff[f].parent, build_as)
-                                                 : tree_stage(k, ff[f].root, ff[f].parent, build_as);
-            finish_levels(fused[f]);
+    size_t k = 0;
+    for (const ServerTrees& sv : servers) k += sv.ranks.size();
+    if (k < 2 || k > BLINK_MAX_RANKS) return BLINK_EINVAL;
+    std::vector<bool> seen(k, false);
+    for (const ServerTrees& sv : servers) {
+        const size_t ks = sv.ranks.size();
+        if (ks < 1 || (sv.trees ? static_cast<size_t>(sv.trees->k) != ks || sv.trees->count() < 1 : ks != 1))
+            return BLINK_EINVAL;
+        for (size_t i = 0; i < ks; ++i) {
+            const int g = sv.ranks[i];
+            if (g < 0 || static_cast<size_t>(g) >= k || seen[g]) return BLINK_EINVAL;
+            if (i > 0 && g <= sv.ranks[i - 1]) return BLINK_EINVAL;  // local order = global order
+            seen[g] = true;
         }
     }
-    Built e = instantiate(edge, flows, chunk);
-    out.steps.resize(e.inst.size());
-    for (size_t i = 0; i < e.inst.size(); ++i) {
-        const StageInst& in = e.inst[i];
-        const StageTmpl& st = e.tmpl[in.tmpl];
-        blink_step_t& s = out.steps[i];
-        s.kind = st.n_load == 2 ? BLINK_STEP_REDUCE : BLINK_STEP_COPY;
-        s.tree = e.where[i].first;
-        s.chunk = e.where[i].second;
-        s.src = st.n_load == 2 ? st.load_rank[1] : st.load_rank[0];
-        s.dst = st.store_rank[0];
-        s.n_deps = in.n_dep;
-        s.deps[0] = in.n_dep > 0 ? in.dep[0] : -1;
-        s.deps[1] = in.n_dep > 1 ? in.dep[1] : -1;
-        s.off = in.off;
-        s.len = in.len;
+    out.k = static_cast<int>(k);
+    out.op = BLINK_OP_ALLREDUCE;
+    out.fusion = fusion;
+    out.n = n;
+    out.chunk = chunk;
+
+    // partitions: the common refinement of the servers' weighted splits
+    std::vector<std::vector<uint64_t>> split(S);
+    std::vector<uint64_t> cuts;
+    for (size_t s = 0; s < S; ++s) {
+        split[s] = servers[s].trees ? split_by_weight(n, servers[s].trees->weight, 4)
+                                    : std::vector<uint64_t>{0, n};
+        cuts.insert(cuts.end(), split[s].begin(), split[s].end());
     }
-    if (fusion == BLINK_FUSE_EDGE) {
-        out.tmpl = std::move(e.tmpl);
-        out.inst = std::move(e.inst);
-    } else {
-        Built f = instantiate(fused, ff, chunk);
-        out.tmpl = std::move(f.tmpl);
-        out.inst = std::move(f.inst);
+    std::sort(cuts.begin(), cuts.end());
+    cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+
+    std::vector<Flow> flows;
+    const std::vector<double> equal(S, 1.0);
+    for (size_t c = 0; c + 1 < cuts.size(); ++c) {
+        const uint64_t lo = cuts[c], hi = cuts[c + 1];
+        ParentVec parent;
+        parent.fill(-2);
+        std::vector<int> root_ids;
+        for (size_t s = 0; s < S; ++s) {
+            const ServerTrees& sv = servers[s];
+            if (!sv.trees) {
+                parent[sv.ranks[0]] = -1;
+                root_ids.push_back(sv.ranks[0]);
+                continue;
+            }
+            size_t t = 0;  // the tree whose non-empty share holds lo
+            for (size_t i = 0; i + 1 < split[s].size(); ++i)
+                if (split[s][i] <= lo && split[s][i] < split[s][i + 1]) t = i;
+            for (size_t v = 0; v < sv.ranks.size(); ++v) {
+                const int p = sv.trees->parent[t][v];
+                parent[sv.ranks[v]] = static_cast<int8_t>(p >= 0 ? sv.ranks[p] : -1);
+            }
+            root_ids.push_back(sv.ranks[sv.trees->root[t]]);
+        }
+        std::sort(root_ids.begin(), root_ids.end());
+        uint16_t all_roots = 0;
+        for (int r : root_ids) all_roots = static_cast<uint16_t>(all_roots | (1u << r));
+        const std::vector<uint64_t> piece = split_by_weight(hi - lo, equal, 4);
+        for (size_t i = 0; i < S; ++i) {
+            if (piece[i] == piece[i + 1]) continue;
+            const int owner = root_ids[i];
+            Flow f;
+            f.parent = parent;
+            for (int r : root_ids) f.parent[r] = static_cast<int8_t>(r == owner ? -1 : owner);
+            f.root = owner;
+            f.lo = lo + piece[i];
+            f.hi = lo + piece[i + 1];
+            f.tree = static_cast<int>(flows.size());
+            f.late = static_cast<uint16_t>(all_roots & ~(1u << owner));
+            flows.push_back(f);
+        }
     }
-    out.max_slots = 1;
-    out.traffic_bytes = 0;
-    out.has_deps = false;
-    for (const StageTmpl& st : out.tmpl) {
-        out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
-        out.has_deps = out.has_deps || st.n_dep > 0;
-    }
-    for (const StageInst& in : out.inst) {
-        const StageTmpl& st = out.tmpl[in.tmpl];
-        out.traffic_bytes += static_cast<uint64_t>(in.len) * 4u * (st.n_load + st.n_store);
-    }
+    out.n_trees = static_cast<int>(flows.size());
+    out.bounds.clear();
+    for (const Flow& f : flows) out.bounds.push_back(f.lo);
+    out.bounds.push_back(n);
+    finish(flows, {}, BLINK_OP_ALLREDUCE, out);
     return BLINK_OK;
 }
 

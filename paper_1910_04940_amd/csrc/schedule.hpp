@@ -64,4 +64,15 @@ std::vector<uint64_t> split_by_weight(uint64_t n, const std::vector<double>& w, 
 blink_status_t make_schedule(const Trees& trees, blink_op_t op, uint64_t n, uint64_t chunk,
                              blink_fusion_t fusion, Schedule& out);
 
+// One server of a multi-server AllReduce (section 3.5): its packed local trees
+// (null for a server with a single rank) and the global ids of its local
+// ranks, ascending.
+struct ServerTrees {
+    const Trees* trees;
+    std::vector<int> ranks;
+};
+
+blink_status_t make_schedule_servers(const std::vector<ServerTrees>& servers, uint64_t n,
+                                     uint64_t chunk, blink_fusion_t fusion, Schedule& out);
+
 }  // namespace blink
