@@ -211,6 +211,9 @@ void blink_schedule_free(blink_schedule_t* s);
 
 /* bufs: HOST array of k DEVICE pointers; each buffer holds at least n_elems
  * 4-byte elements, is 16-byte aligned and overlaps no other.  In place.
+ * (Performance only: buffers that lie at multiples of a large power of two
+ * from one another put equal offsets of all ranks on the same HBM channel and
+ * bank; a few tens of KiB of extra distance avoids that.)
  * The call enqueues one kernel on `stream` (a hipStream_t passed as void*;
  * null = the default stream) and returns without waiting; when the stream
  * reaches the end of that kernel every bufs[i] holds the result:

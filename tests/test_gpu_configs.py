@@ -38,15 +38,27 @@ def bits(a):
 
 
 @pytest.mark.parametrize("fusion", ["tree", "node", "edge"])
-def test_headline_8_ranks_cube_mesh_256MiB_fp32(dev, fusion):
-    """The benchmark's workload, every element of every rank against the oracle."""
+@pytest.mark.parametrize("layout", ["separate", "slab"])
+def test_headline_8_ranks_cube_mesh_256MiB_fp32(dev, fusion, layout):
+    """The benchmark's workload, every element of every rank against the oracle,
+    with one allocation per rank buffer and with the benchmark's own placement
+    (one allocation, consecutive rank buffers a little further apart than the
+    payload); there the gaps between the buffers must come back untouched."""
+    import bench
     top = si.hybrid_cube_mesh()
     n, chunk = 1 << 26, 1 << 18
     trees = pack(top, 0)
     roots, parents, w = trees.as_lists()
     assert trees.count == 4 and w == [1.0] * 4
     x = [si.payload(0, r, n, "uniform", "fp32") for r in range(8)]
-    bufs = [torch.from_numpy(a).to(dev) for a in x]
+    if layout == "separate":
+        bufs = [torch.from_numpy(a).to(dev) for a in x]
+    else:
+        stride = n + bench.RANK_PAD_BYTES // 4
+        slab = torch.full((8 * stride,), float("nan"), dtype=torch.float32, device=dev)
+        bufs = [slab[r * stride: r * stride + n] for r in range(8)]
+        for b, a in zip(bufs, x):
+            b.copy_(torch.from_numpy(a))
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, FUSION[fusion])
     assert sched.num_steps == 3584
     bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
@@ -57,6 +69,8 @@ def test_headline_8_ranks_cube_mesh_256MiB_fp32(dev, fusion):
         rel = np.max(np.abs(got - x[0]) / np.maximum(np.abs(x[0]), np.finfo(np.float32).tiny))
         assert rel <= 1e-6
         assert np.array_equal(bits(got), bits(x[0])), f"rank {r}"
+        if layout == "slab":
+            assert bool(torch.isnan(slab[r * stride + n:(r + 1) * stride]).all()), f"gap after rank {r}"
 
 
 @pytest.mark.parametrize("fusion", ["tree", "edge"])
