@@ -41,7 +41,15 @@
 namespace blink {
 
 constexpr int kLanes = 64;        // one wavefront per workgroup
-constexpr int kMaxColumns = 16;   // 128-bit columns a lane holds in registers at once (ranks read x U)
+// 128-bit columns a lane holds in registers (and LDS slots) at once = ranks
+// read x U: 32 (32 KiB of LDS per wave) for payloads large enough to stream,
+// which run fastest with few waves that each keep many bytes in flight
+// (measured on 8 x 256 MiB, against 16 columns and one more wave per CU:
+// whole-tree stages 0.690 -> 0.680 ms, per-node stages 1.35 -> 1.19 ms,
+// per-edge stages 1.52 -> 1.41 ms); 16 where every wave that fits is wanted
+// (small payloads).
+constexpr int kColumnsMany = 16;
+constexpr int kColumnsStream = 32;
 constexpr unsigned kMinTile = kLanes * 4;   // elements: one column per lane
 constexpr unsigned kMaxTile = 65536;        // elements
 // One ticket counter serves the whole chip; it sustains roughly 80 draws per
@@ -195,12 +203,13 @@ __device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, C
     }
 }
 
-// Pick U for a stage that reads N ranks: the largest power of two with
-// N * U <= kMaxColumns that does not exceed the tile (cols = tile columns per lane).
-template <typename T, int N, int LD, int ST>
+// Pick U for a stage that reads N ranks: the largest power of two (at most 16)
+// with N * U <= COLS that does not exceed the tile (cols = tile columns per lane).
+template <typename T, int N, int COLS, int LD, int ST>
 __device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
                                           unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
-    constexpr int kBudget = N <= 1 ? 16 : (N <= 2 ? 8 : (N <= 4 ? 4 : (N <= 8 ? 2 : 1)));
+    constexpr int kFit = COLS / N;
+    constexpr int kBudget = kFit >= 16 ? 16 : (kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1)));
     if constexpr (kBudget >= 16)
         if (cols >= 16) return run_vec<T, N, 16, LD, ST>(slots, p, st, byte_off, bytes, lane);
     if constexpr (kBudget >= 8)
@@ -212,11 +221,11 @@ __device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p,
     run_vec<T, N, 1, LD, ST>(slots, p, st, byte_off, bytes, lane);
 }
 
-template <typename T, int LD, int ST>
+template <typename T, int COLS, int LD, int ST>
 __device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
                                             unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
     switch (BLINK_TMPL(st, n_load, 0)) {
-#define BLINK_CASE(N) case N: run_vec_n<T, N, LD, ST>(slots, p, st, byte_off, bytes, cols, lane); break;
+#define BLINK_CASE(N) case N: run_vec_n<T, N, COLS, LD, ST>(slots, p, st, byte_off, bytes, cols, lane); break;
         BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
         BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
         BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
@@ -266,11 +275,12 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
 //          use system-scope cache policy (loads bypass, stores write through),
 //          so the hand-over needs no L2 write-back or invalidate, only "my
 //          stores have completed" before the counter is bumped.
+// COLS: the column budget (LDS slots per lane).
 // The by-value argument is only there to size the kernel-argument segment; it is
 // read through the constant address space (see ConstParams).
-template <typename T, bool COHERENT>
+template <typename T, bool COHERENT, int COLS>
 __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
-    __shared__ U4 slots[kMaxColumns * kLanes];  // 16 KiB: 16 columns per lane
+    __shared__ U4 slots[COLS * kLanes];  // 16 or 32 KiB: COLS columns per lane
     constexpr int LD = COHERENT ? kPolicySystem : kPolicyStream;
     constexpr int ST = COHERENT ? kPolicySystem : kPolicyStream;
     const int lane = threadIdx.x;
@@ -283,7 +293,7 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     const unsigned tiles_per_chunk = p->tiles_per_chunk;
     const unsigned tile_shift = p->tile_shift;
     const unsigned tile_elems = 1u << tile_shift;
-    const unsigned cols = min(tile_elems / kMinTile, static_cast<unsigned>(kMaxColumns));
+    const unsigned cols = min(tile_elems / kMinTile, static_cast<unsigned>(COLS));
     const unsigned group = p->group;
     const unsigned n_inst = static_cast<unsigned>(n_items / tiles_per_chunk);
 
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
             const unsigned long long e0 = lo_e;  // first element of the tile
             if ((e0 & 3ull) == 0) {
                 const unsigned vec_bytes = (tlen >> 2) * 16u;
-                if (vec_bytes) run_vec_any<T, LD, ST>(slots, p, st, e0 * 4ull, vec_bytes, cols, lane);
+                if (vec_bytes) run_vec_any<T, COLS, LD, ST>(slots, p, st, e0 * 4ull, vec_bytes, cols, lane);
                 const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
                 if (rem)
                     run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + vec_bytes,
@@ -399,9 +409,16 @@ namespace {
 
 using KernelFn = void (*)(const KParams);
 
-KernelFn pick_kernel(blink_dtype_t dtype, bool coherent) {
-    if (dtype == BLINK_FP32) return coherent ? blink_consume<float, true> : blink_consume<float, false>;
-    return coherent ? blink_consume<unsigned, true> : blink_consume<unsigned, false>;
+template <typename T>
+KernelFn pick_kernel_of(bool coherent, bool many_waves) {
+    if (coherent)
+        return many_waves ? blink_consume<T, true, kColumnsMany> : blink_consume<T, true, kColumnsStream>;
+    return many_waves ? blink_consume<T, false, kColumnsMany> : blink_consume<T, false, kColumnsStream>;
+}
+
+KernelFn pick_kernel(blink_dtype_t dtype, bool coherent, bool many_waves) {
+    return dtype == BLINK_FP32 ? pick_kernel_of<float>(coherent, many_waves)
+                               : pick_kernel_of<unsigned>(coherent, many_waves);
 }
 
 // word 0: the ticket counter; then one counter per stage instance, kCounterStride words apart
@@ -437,6 +454,7 @@ blink_status_t reset_progress(blink_schedule* h) {
     h->epoch = 0;
     h->ticket_base = 0;
     h->tile_elems = 0;
+    h->tile_final = false;
     if (h->device < 0) return BLINK_OK;
     BLINK_HIP(hipDeviceSynchronize());
     BLINK_HIP(hipMemset(h->d_counters, 0, counter_bytes(h->s)));
@@ -470,7 +488,25 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     if (n == 0 || s.inst.empty()) return BLINK_OK;
     if (blink_status_t st = upload(h)) return st;
 
-    KernelFn fn = pick_kernel(dtype, s.has_deps);
+    // Tile size, fixed at the first call (the progress counters count tiles):
+    // large enough that a ticket moves about kTicketBytes.  A payload too small
+    // to give a streaming grid a few dozen such tickets per CU is latency-bound
+    // instead ("wide"): then all the waves that fit are used and the tile
+    // shrinks until about every other wave has one.
+    uint64_t work = 0;  // elements x stages
+    if (!h->tile_final)
+        for (const StageInst& in : s.inst) work += in.len;
+    if (h->tile_elems == 0) {
+        const uint64_t bytes_per_elem = std::max<uint64_t>(1, s.traffic_bytes / std::max<uint64_t>(1, work));
+        // the power of two nearest (in ratio) to kTicketBytes / bytes_per_elem
+        unsigned tile = kMinTile;
+        while (tile < kMaxTile && 2ull * tile * tile * bytes_per_elem * bytes_per_elem <
+                                      static_cast<uint64_t>(kTicketBytes) * kTicketBytes)
+            tile *= 2;
+        h->wide = work / tile < 24ull * h->n_cu;
+        h->tile_elems = tile;
+    }
+    KernelFn fn = pick_kernel(dtype, s.has_deps, h->wide);
     int& cached = h->occupancy[dtype == BLINK_FP32];
     if (cached == 0) {
         BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, 0));
@@ -479,28 +515,18 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
             return BLINK_EHIP;
         }
     }
-    // A few waves per CU, each with ~16 KiB of loads in flight, saturate HBM;
-    // more waves only add ticket and polling traffic and disturb DRAM page
-    // locality (measured: 3 is best for pure streaming, 4 when stages wait).
-    int per_cu = std::min(cached, s.has_deps ? 4 : 3);
-    if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
-
-    // Tile size, fixed at the first call (the progress counters count tiles):
-    // large enough that a ticket moves about kTicketBytes.  A payload too small
-    // to give every wave several such tickets is latency-bound instead: then
-    // all the waves that fit are used and the tile shrinks until about every
-    // other wave has one.
-    if (h->tile_elems == 0) {
-        uint64_t work = 0;  // elements x stages
-        for (const StageInst& in : s.inst) work += in.len;
-        const uint64_t bytes_per_elem = std::max<uint64_t>(1, s.traffic_bytes / std::max<uint64_t>(1, work));
-        unsigned tile = kMinTile;
-        while (tile < kMaxTile && static_cast<uint64_t>(tile) * bytes_per_elem < kTicketBytes) tile *= 2;
-        h->wide = work / tile < 8ull * per_cu * h->n_cu;
+    if (!h->tile_final) {
+        unsigned tile = h->tile_elems;
         if (h->wide)
             while (tile > kMinTile && work / tile < static_cast<uint64_t>(cached) * h->n_cu / 2) tile /= 2;
         h->tile_elems = h->tile_override ? h->tile_override : tile;
+        h->tile_final = true;
     }
+    // A few waves per CU, each with 32 KiB of loads in flight, saturate HBM;
+    // more waves only add ticket and polling traffic (measured best: 2, and 3
+    // where stages wait for one another and read more than two ranks).
+    int per_cu = std::min(cached, s.has_deps && s.max_slots > 2 ? 3 : 2);
+    if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
     if (h->wide && h->wg_per_cu == 0) per_cu = cached;
     const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
     const unsigned tile = h->tile_elems;

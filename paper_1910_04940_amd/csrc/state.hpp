@@ -17,6 +17,7 @@ struct blink_schedule {
     int wg_per_cu = 0;            // launch override (0 = automatic)
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
     unsigned tile_elems = 0;      // elements per tile in use (0 = not chosen yet)
+    bool tile_final = false;      // tile_elems has had its small-payload adjustment
     bool wide = false;            // small payload: use every wave that fits
     int occupancy[2] = {0, 0};    // waves per CU, cached per dtype
     unsigned last_grid = 0;
