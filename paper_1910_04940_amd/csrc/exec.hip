@@ -11,9 +11,9 @@
 // A tile (256..65536 elements, chosen per schedule) is cut into sub-tiles; a
 // sub-tile of a stage is processed in three phases by the 64 lanes, each owning
 // U 128-bit columns, where U is as large as the stage allows under a budget of
-// 16 columns in registers (a stage that reads 8 ranks gets U = 2, a plain copy
-// U = 16), so that every wave keeps about 16 KiB of loads in flight whatever
-// the stage looks like:
+// 32 columns in registers and LDS (a stage that reads 8 ranks gets U = 4, a
+// plain copy the maximum, 16), so that every wave keeps up to 32 KiB of loads
+// in flight whatever the stage looks like (16 columns for small payloads):
 //   1. load the sub-tile from every rank the stage reads; all loads are issued
 //      before the first is consumed, then parked in per-lane LDS slots;
 //   2. run the stage's micro-program (acc = slot / acc += slot / slot = acc)
