@@ -523,9 +523,11 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         h->tile_final = true;
     }
     // A few waves per CU, each with 32 KiB of loads in flight, saturate HBM;
-    // more waves only add ticket and polling traffic (measured best: 2, and 3
-    // where stages wait for one another and read more than two ranks).
-    int per_cu = std::min(cached, s.has_deps && s.max_slots > 2 ? 3 : 2);
+    // more waves only add ticket and polling traffic.  Measured best: 2, and 3
+    // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms)
+    // or where stages wait for one another and read more than two ranks.
+    const bool read_heavy = s.read_bytes >= 2 * (s.traffic_bytes - s.read_bytes);
+    int per_cu = std::min(cached, read_heavy || (s.has_deps && s.max_slots > 2) ? 3 : 2);
     if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
     if (h->wide && h->wg_per_cu == 0) per_cu = cached;
     const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;

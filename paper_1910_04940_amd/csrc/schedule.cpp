@@ -404,6 +404,7 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
     }
     out.max_slots = 1;
     out.traffic_bytes = 0;
+    out.read_bytes = 0;
     out.has_deps = false;
     for (const StageTmpl& st : out.tmpl) {
         out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
@@ -412,6 +413,7 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
     for (const StageInst& in : out.inst) {
         const StageTmpl& st = out.tmpl[in.tmpl];
         out.traffic_bytes += static_cast<uint64_t>(in.len) * 4u * (st.n_load + st.n_store);
+        out.read_bytes += static_cast<uint64_t>(in.len) * 4u * st.n_load;
     }
 }
 

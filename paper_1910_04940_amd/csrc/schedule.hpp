@@ -54,7 +54,8 @@ struct Schedule {
     std::vector<StageInst> inst;         // execution (ticket) order; dependencies point backwards
     uint32_t max_slots = 1;              // largest n_load
     bool has_deps = false;               // some stage waits for another
-    uint64_t traffic_bytes = 0;
+    uint64_t traffic_bytes = 0;          // bytes read plus written in rank buffers per call
+    uint64_t read_bytes = 0;             // the part of it that is read
 };
 
 // Exact floor(n * (w_0+..+w_{t-1}) / (w_0+..+w_{T-1})) rounded down to a multiple of
