@@ -1,6 +1,7 @@
 // extern "C" boundary: argument checks, handle management, no exceptions out.
 #include <cmath>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "state.hpp"
@@ -27,13 +28,10 @@ blink_status_t blink_pack_trees(int k, int m, const int32_t* src, const int32_t*
     if (!out) return BLINK_EINVAL;
     *out = nullptr;
     BLINK_GUARD_BEGIN
-    blink_trees_t* h = new blink_trees_t();
+    std::unique_ptr<blink_trees_t> h(new blink_trees_t());
     const blink_status_t st = blink::pack_trees(k, m, src, dst, cap, root, eps, prune_tol, h->t);
-    if (st != BLINK_OK) {
-        delete h;
-        return st;
-    }
-    *out = h;
+    if (st != BLINK_OK) return st;
+    *out = h.release();
     return BLINK_OK;
     BLINK_GUARD_END
 }
@@ -44,7 +42,7 @@ blink_status_t blink_trees_from_arrays(int k, int T, const int32_t* roots, const
     *out = nullptr;
     if (k < 2 || k > BLINK_MAX_RANKS || T < 1 || !roots || !parent || !weight) return BLINK_EINVAL;
     BLINK_GUARD_BEGIN
-    blink_trees_t* h = new blink_trees_t();
+    std::unique_ptr<blink_trees_t> h(new blink_trees_t());
     h->t.k = k;
     for (int t = 0; t < T; ++t) {
         blink::ParentVec p;
@@ -55,15 +53,12 @@ blink_status_t blink_trees_from_arrays(int k, int T, const int32_t* roots, const
             if (q < -1 || q >= k) ok = false;
             p[v] = static_cast<int8_t>(q);
         }
-        if (!ok || !blink::is_spanning_tree(k, roots[t], p)) {
-            delete h;
-            return BLINK_EINVAL;
-        }
+        if (!ok || !blink::is_spanning_tree(k, roots[t], p)) return BLINK_EINVAL;
         h->t.root.push_back(roots[t]);
         h->t.parent.push_back(p);
         h->t.weight.push_back(weight[t]);
     }
-    *out = h;
+    *out = h.release();
     return BLINK_OK;
     BLINK_GUARD_END
 }
@@ -97,13 +92,10 @@ blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, si
     *out = nullptr;
     if (!trees) return BLINK_EINVAL;
     BLINK_GUARD_BEGIN
-    blink_schedule_t* h = new blink_schedule_t();
+    std::unique_ptr<blink_schedule_t> h(new blink_schedule_t());
     const blink_status_t st = blink::make_schedule(trees->t, op, n_elems, chunk_elems, fusion, h->s);
-    if (st != BLINK_OK) {
-        delete h;
-        return st;
-    }
-    *out = h;
+    if (st != BLINK_OK) return st;
+    *out = h.release();
     return BLINK_OK;
     BLINK_GUARD_END
 }
@@ -125,13 +117,10 @@ blink_status_t blink_make_schedule_servers(int n_servers, const blink_trees_t* c
         servers[s].ranks.assign(ranks + at, ranks + at + ks);
         at += ks;
     }
-    blink_schedule_t* h = new blink_schedule_t();
+    std::unique_ptr<blink_schedule_t> h(new blink_schedule_t());
     const blink_status_t st = blink::make_schedule_servers(servers, n_elems, chunk_elems, fusion, h->s);
-    if (st != BLINK_OK) {
-        delete h;
-        return st;
-    }
-    *out = h;
+    if (st != BLINK_OK) return st;
+    *out = h.release();
     return BLINK_OK;
     BLINK_GUARD_END
 }
