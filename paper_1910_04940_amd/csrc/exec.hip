@@ -143,8 +143,31 @@ __device__ __forceinline__ unsigned tmpl_byte(ConstTmpl st, unsigned byte_index)
 // are dropped by the hardware range check, so ragged ends need no branches.
 // The cache-policy bits of each access are chosen per kernel flavour (below).
 constexpr int kRawDword3 = 0x00020000;  // raw 32-bit data format, no swizzle (gfx9 family)
+constexpr int kPolicyDefault = 0;
 constexpr int kPolicyStream = 2;        // nt: streamed once, do not keep in cache
+constexpr int kPolicyThrough = 16;      // sc1: agent scope, stores written through
 constexpr int kPolicySystem = 17;       // sc0 sc1: bypass / write through every cache level
+
+// Kernel flavours: the cache policy of rank-buffer loads and stores.
+enum Flavour : int {
+    kHandOver = 0,    // stages hand chunks over to one another (see blink_consume)
+    kBalanced = 1,    // streaming, about as many bytes read as written
+    kWriteHeavy = 2,  // streaming, at least twice as many bytes written as read
+    kReadHeavy = 3,   // streaming, at least twice as many bytes read as written
+};
+// Measured on 8 x 256 MiB, fp32 (load policy, store policy -> ms):
+//   AllReduce  (nt, nt) 0.676  (nt, nt sc1) 0.668  (default, nt sc1) 0.688  (nt, sc1) 0.676
+//   Reduce     (nt, nt) 0.411  (nt, sc1) 0.383     (default, any) 0.44-0.46
+//   Broadcast  (nt, nt) 0.383  (default, nt sc1) 0.297  (default, nt) 0.304
+template <int FLAVOUR>
+struct Policy {
+    static constexpr int kLoad = FLAVOUR == kHandOver ? kPolicySystem
+                                 : (FLAVOUR == kWriteHeavy ? kPolicyDefault : kPolicyStream);
+    static constexpr int kStore = FLAVOUR == kHandOver     ? kPolicySystem
+                                  : FLAVOUR == kWriteHeavy ? (kPolicyStream | kPolicyThrough)
+                                  : FLAVOUR == kReadHeavy  ? kPolicyThrough
+                                                           : kPolicyStream;
+};
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rank_window(ConstParams p, unsigned rank,
                                                               unsigned long long byte_off, unsigned bytes) {
@@ -266,23 +289,24 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
     }
 }
 
-// T: element type (float, or unsigned for wrap-around int32).  COHERENT selects
+// T: element type (float, or unsigned for wrap-around int32).  FLAVOUR selects
 // how data is exchanged between stages:
-//   false  the schedule has no stage that waits for another (TREE fusion):
-//          streaming (nt) accesses, no fences;
-//   true   stages hand chunks over to each other, possibly across XCDs whose L2
-//          caches are not coherent with one another: all rank-buffer accesses
+//   streaming flavours: the schedule has no stage that waits for another (TREE
+//          fusion): streaming accesses with the policy measured best for the
+//          schedule's mix of reads and writes, no fences;
+//   kHandOver: stages hand chunks over to each other, possibly across XCDs whose
+//          L2 caches are not coherent with one another: all rank-buffer accesses
 //          use system-scope cache policy (loads bypass, stores write through),
 //          so the hand-over needs no L2 write-back or invalidate, only "my
 //          stores have completed" before the counter is bumped.
 // COLS: the column budget (LDS slots per lane).
 // The by-value argument is only there to size the kernel-argument segment; it is
 // read through the constant address space (see ConstParams).
-template <typename T, bool COHERENT, int COLS>
+template <typename T, int FLAVOUR, int COLS>
 __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     __shared__ U4 slots[COLS * kLanes];  // 16 or 32 KiB: COLS columns per lane
-    constexpr int LD = COHERENT ? kPolicySystem : kPolicyStream;
-    constexpr int ST = COHERENT ? kPolicySystem : kPolicyStream;
+    constexpr int LD = Policy<FLAVOUR>::kLoad;
+    constexpr int ST = Policy<FLAVOUR>::kStore;
     const int lane = threadIdx.x;
     ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
     unsigned long long* const ticket = p->ticket;
@@ -409,16 +433,22 @@ namespace {
 
 using KernelFn = void (*)(const KParams);
 
-template <typename T>
-KernelFn pick_kernel_of(bool coherent, bool many_waves) {
-    if (coherent)
-        return many_waves ? blink_consume<T, true, kColumnsMany> : blink_consume<T, true, kColumnsStream>;
-    return many_waves ? blink_consume<T, false, kColumnsMany> : blink_consume<T, false, kColumnsStream>;
+template <typename T, int COLS>
+KernelFn pick_kernel_of(int flavour) {
+    switch (flavour) {
+        case kHandOver: return blink_consume<T, kHandOver, COLS>;
+        case kWriteHeavy: return blink_consume<T, kWriteHeavy, COLS>;
+        case kReadHeavy: return blink_consume<T, kReadHeavy, COLS>;
+        default: return blink_consume<T, kBalanced, COLS>;
+    }
 }
 
-KernelFn pick_kernel(blink_dtype_t dtype, bool coherent, bool many_waves) {
-    return dtype == BLINK_FP32 ? pick_kernel_of<float>(coherent, many_waves)
-                               : pick_kernel_of<unsigned>(coherent, many_waves);
+KernelFn pick_kernel(blink_dtype_t dtype, int flavour, bool many_waves) {
+    if (dtype == BLINK_FP32)
+        return many_waves ? pick_kernel_of<float, kColumnsMany>(flavour)
+                          : pick_kernel_of<float, kColumnsStream>(flavour);
+    return many_waves ? pick_kernel_of<unsigned, kColumnsMany>(flavour)
+                      : pick_kernel_of<unsigned, kColumnsStream>(flavour);
 }
 
 // word 0: the ticket counter; then one counter per stage instance, kCounterStride words apart
@@ -506,7 +536,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         h->wide = work / tile < 24ull * h->n_cu;
         h->tile_elems = tile;
     }
-    KernelFn fn = pick_kernel(dtype, s.has_deps, h->wide);
+    const uint64_t write_bytes = s.traffic_bytes - s.read_bytes;
+    const bool read_heavy = s.read_bytes >= 2 * write_bytes, write_heavy = write_bytes >= 2 * s.read_bytes;
+    const int flavour = s.has_deps ? kHandOver : (read_heavy ? kReadHeavy : (write_heavy ? kWriteHeavy : kBalanced));
+    KernelFn fn = pick_kernel(dtype, flavour, h->wide);
     int& cached = h->occupancy[dtype == BLINK_FP32];
     if (cached == 0) {
         BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, 0));
@@ -526,7 +559,6 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     // more waves only add ticket and polling traffic.  Measured best: 2, and 3
     // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms)
     // or where stages wait for one another and read more than two ranks.
-    const bool read_heavy = s.read_bytes >= 2 * (s.traffic_bytes - s.read_bytes);
     int per_cu = std::min(cached, read_heavy || (s.has_deps && s.max_slots > 2) ? 3 : 2);
     if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
     if (h->wide && h->wg_per_cu == 0) per_cu = cached;
