@@ -159,9 +159,10 @@ enum Flavour : int {
 //   AllReduce  (nt, nt) 0.676  (nt, nt sc1) 0.668  (default, nt sc1) 0.688  (nt, sc1) 0.676
 //   Reduce     (nt, nt) 0.411  (nt, sc1) 0.383     (default, any) 0.44-0.46
 //   Broadcast  (nt, nt) 0.383  (default, nt sc1) 0.297  (default, nt) 0.304
+//   per-edge AllReduce  (sc0 sc1, sc0 sc1) 1.417  (sc0 sc1 nt, sc0 sc1) 1.337  nt on stores 1.65-1.72
 template <int FLAVOUR>
 struct Policy {
-    static constexpr int kLoad = FLAVOUR == kHandOver ? kPolicySystem
+    static constexpr int kLoad = FLAVOUR == kHandOver ? (kPolicySystem | kPolicyStream)
                                  : (FLAVOUR == kWriteHeavy ? kPolicyDefault : kPolicyStream);
     static constexpr int kStore = FLAVOUR == kHandOver     ? kPolicySystem
                                   : FLAVOUR == kWriteHeavy ? (kPolicyStream | kPolicyThrough)
@@ -296,7 +297,8 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
 //          schedule's mix of reads and writes, no fences;
 //   kHandOver: stages hand chunks over to each other, possibly across XCDs whose
 //          L2 caches are not coherent with one another: all rank-buffer accesses
-//          use system-scope cache policy (loads bypass, stores write through),
+//          use system-scope cache policy (loads bypass, stores write through;
+//          the loads also carry the streaming hint, which changes no scope),
 //          so the hand-over needs no L2 write-back or invalidate, only "my
 //          stores have completed" before the counter is bumped.
 // COLS: the column budget (LDS slots per lane).
