@@ -26,7 +26,10 @@
  *     passes in; the library never frees or reallocates caller memory.
  *   - A schedule keeps device-side progress counters: it may be used by many
  *     calls one after another on ONE stream at a time.  Two calls that overlap
- *     in time on the same schedule race.
+ *     in time on the same schedule race.  Every launch carries the number of
+ *     the call on its schedule, so a call must not be recorded into a HIP graph
+ *     (a replay would repeat a number); the first call on a schedule also
+ *     allocates, which a capturing stream forbids anyway.
  *   - At most BLINK_MAX_RANKS ranks.
  */
 #ifndef BLINK_H
