@@ -170,3 +170,59 @@ def test_config5_sixteen_rank_switch_1GiB_per_rank(dev):
         want = ox.tree_order_allreduce(xs, [roots[t]], [parents[t]], [1.0])
         got = bufs[3][a:a + width].cpu().numpy()
         assert np.array_equal(bits(got), bits(want)), f"slice at {a} (tree {t})"
+
+
+# ---- every kernel flavour at streaming size -------------------------------------------
+# Large payloads run other kernel instantiations (32 columns per lane, cache
+# policy by the schedule's read/write mix) than the small ones the element-by-
+# element tests mostly use.  A whole-tree schedule streams from about
+# 6144 tickets x 4096 elements = 25 M elements on, hence 2^25 per rank here.
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+@pytest.mark.parametrize("coll", ["reduce", "broadcast", "allgather"])
+def test_read_heavy_and_write_heavy_collectives_at_streaming_size(dev, dtype, coll):
+    top = si.hybrid_cube_mesh()
+    n, chunk, k = 1 << 25, 1 << 18, 8
+    trees = pack(top, 0)
+    roots, parents, w = trees.as_lists()
+    code = bl.BLINK_INT32 if dtype == "int32" else bl.BLINK_FP32
+    x = [si.payload(31, r, n, "int" if dtype == "int32" else "uniform", dtype) for r in range(k)]
+    bufs = [torch.from_numpy(a).to(dev) for a in x]
+    if coll == "reduce":
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_REDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+        bl.blink_reduce(bufs, n, code, bl.BLINK_SUM, sched, stream())
+        want = ox.tree_order_allreduce(x, roots, parents, w)
+        if dtype == "int32":
+            assert np.array_equal(want, ox.allreduce_int32_definition(x))
+        torch.cuda.synchronize()
+        assert bufs[0].cpu().numpy().tobytes() == want.tobytes()      # every tree is rooted at 0
+        for r in range(1, k):                                          # a whole-tree pass writes the root only
+            assert bufs[r].cpu().numpy().tobytes() == x[r].tobytes()
+    elif coll == "broadcast":
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, n, chunk, bl.BLINK_FUSE_TREE)
+        bl.blink_broadcast(bufs, n, code, sched, stream())
+        want = ox.broadcast_definition(x, roots, w)
+        torch.cuda.synchronize()
+        for b in bufs:
+            assert b.cpu().numpy().tobytes() == want.tobytes()
+    else:
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLGATHER, n, chunk, bl.BLINK_FUSE_TREE)
+        bl.blink_allgather(bufs, n, code, sched, stream())
+        want = ox.allgather_definition(x)
+        torch.cuda.synchronize()
+        for b in bufs:
+            assert b.cpu().numpy().tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("fusion", ["edge", "node"])
+def test_int32_hand_over_kernels_at_streaming_size(dev, fusion):
+    top = si.hybrid_cube_mesh()
+    n, chunk = 1 << 24, 1 << 18
+    trees = pack(top, 0)
+    x = [si.payload(32, r, n, "int", "int32") for r in range(8)]
+    bufs = [torch.from_numpy(a).to(dev) for a in x]
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, FUSION[fusion])
+    bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream())
+    want = ox.allreduce_int32_definition(x)
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert np.array_equal(b.cpu().numpy(), want)
