@@ -10,9 +10,9 @@ struct blink_schedule {
     int device = -1;              // HIP device holding the tables; -1 = not uploaded yet
     void* d_tmpl = nullptr;       // StageTmpl[]
     void* d_inst = nullptr;       // StageInst[]
-    void* d_counters = nullptr;   // u64 ticket, then one u64 of finished tiles per instance
+    void* d_counters = nullptr;   // u64 ticket counters, then one u64 of finished tiles per instance
     uint64_t epoch = 0;           // calls made so far; counters hold epoch * tiles
-    uint64_t ticket_base = 0;     // value of the ticket counter when the next call starts
+    uint64_t ticket_base[16] = {};  // value of each ticket counter when the next call starts
     int n_cu = 0;
     int wg_per_cu = 0;            // launch override (0 = automatic)
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
