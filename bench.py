@@ -213,7 +213,10 @@ def main():
                                "node": "per-node: one pass per fan-in and per fan-out",
                                "tree": "staged minimum: every rank buffer read once and written once, 8k B/elt"}[args.fusion],
                 "kernel": "blink_consume", "avg_kernel_ms": avg_kernel_ms,
+                "median_kernel_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
                 "min_kernel_ms": min(kernel_ms)}
+    if roofline["traffic"] is not None:   # the counters' bytes over this run's kernel time
+        roofline["traffic_rate_GBs"] = roofline["traffic"] / (avg_kernel_ms * 1e-3) / 1e9
 
     out = {
         "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
