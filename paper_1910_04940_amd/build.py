@@ -8,11 +8,13 @@ C++ program simply links its own libamdhip64)."""
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libblink.so")
-SOURCES = ["api.cpp", "pack.cpp", "schedule.cpp", "miad.cpp", "exec.hip"]
+SOURCES = ["kernel_f32_stream.hip", "kernel_i32_stream.hip", "kernel_f32_many.hip", "kernel_i32_many.hip", "exec.hip",
+           "api.cpp", "pack.cpp", "schedule.cpp", "miad.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-c",
     "-fno-gpu-flush-denormals-to-zero",      # fp32 subnormals are ordinary addends
@@ -26,14 +28,17 @@ def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    objs = []
-    for s in SOURCES:
-        obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
-        cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s), "-o", obj]
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        cmd = [hipcc] + FLAGS + [os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True, stderr=None if verbose else subprocess.DEVNULL)
-        objs.append(obj)
+        return obj
+
+    # the kernel instantiation units take about half a minute each: side by side
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     link = [os.environ.get("CXX", "g++"), "-shared", "-o", LIB] + objs
     if verbose:
         print(" ".join(link), flush=True)

@@ -1,458 +1,8 @@
-// The device side: one persistent gfx950 kernel that consumes the stage list of
-// all trees concurrently (paper sections 3.3, 4.1, 4.2.1, 4.2.2), and its launcher.
-//
-// A workgroup is ONE 64-lane wavefront: nothing in the kernel needs a
-// workgroup barrier, and a wave that waits for a dependency holds up nobody
-// else.  Work unit: (stage instance, tile).  Waves draw units from one ticket
-// counter in the schedule's execution order, so every unit a wave might have
-// to wait for has already been drawn by a wave that is running: waiting can
-// never deadlock, whatever the grid size.
-//
-// A tile (256..65536 elements, chosen per schedule) is cut into sub-tiles; a
-// sub-tile of a stage is processed in three phases by the 64 lanes, each owning
-// U 128-bit columns, where U is as large as the stage allows under a budget of
-// 32 columns in registers and LDS (a stage that reads 8 ranks gets U = 4, a
-// plain copy the maximum, 16), so that every wave keeps up to 32 KiB of loads
-// in flight whatever the stage looks like (16 columns for small payloads):
-//   1. load the sub-tile from every rank the stage reads; all loads are issued
-//      before the first is consumed, then parked in per-lane LDS slots;
-//   2. run the stage's micro-program (acc = slot / acc += slot / slot = acc)
-//      over the slots: this is where the tree's summation order is applied,
-//      with partial sums staged in LDS instead of going back to HBM;
-//   3. store acc to every rank the stage writes.
-// LDS slots are private to a lane (lane l only touches column l).
-//
-// Chunk-granular hand-over (the paper's per-chunk event): a stage instance has
-// a 64-bit counter of finished tiles.  Counters are never reset; call number e
-// on a schedule waits for e * tiles.  Data handed from stage to stage travels
-// with system-scope cache policy (see blink_consume), the counters with
-// agent-scope atomics.
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
-#include <cstddef>
-#include <cstdio>
-#include <type_traits>
-#include <vector>
-
-#include "schedule.hpp"
-#include "state.hpp"
+// The launcher of the persistent kernel (see kernel.hpp): device-side tables and
+// counters of a schedule, the choice of tile size, grid and kernel flavour, the launch.
+#include "kernel.hpp"
 
 namespace blink {
-
-constexpr int kLanes = 64;        // one wavefront per workgroup
-// 128-bit columns a lane holds in registers (and LDS slots) at once = ranks
-// read x U: 32 (32 KiB of LDS per wave) for payloads large enough to stream,
-// which run fastest with few waves that each keep many bytes in flight
-// (measured on 8 x 256 MiB, against 16 columns and one more wave per CU:
-// whole-tree stages 0.690 -> 0.680 ms, per-node stages 1.35 -> 1.19 ms,
-// per-edge stages 1.52 -> 1.41 ms); 16 where every wave that fits is wanted
-// (small payloads).
-constexpr int kColumnsMany = 16;
-constexpr int kColumnsStream = 32;
-constexpr unsigned kMinTile = kLanes * 4;   // elements: one column per lane
-constexpr unsigned kMaxTile = 65536;        // elements
-// One ticket counter sustains roughly 80 draws per microsecond.  A ticket of a
-// dependency-free schedule, which draws from one counter, should therefore move
-// about this many bytes (6 TB/s are then 47 draws per microsecond).
-constexpr unsigned kTicketBytes = 128 * 1024;
-// Progress counters sit 256 bytes apart: the few counters that are hot at any
-// moment then live in different cache lines and memory channels, so thousands
-// of polling waves do not pile up on one of them.
-constexpr int kCounterStride = 32;  // in 8-byte words
-// Tickets can be dealt from several counters ("queues"), ticket t from queue
-// t mod n: one counter sustains ~83 fetch-adds per microsecond however many
-// waves ask, n counters in different memory channels n times that (measured:
-// 540 per microsecond with 8, 1040 with 16).  Schedules whose stages wait for
-// one another use 4 queues and half-size tickets (per-edge AllReduce on
-// 8 x 256 MiB: 1.336 -> 1.277 ms, per-node 1.169 -> 1.125 ms).  Dependency-free
-// streaming keeps ONE queue: there the single counter is no bottleneck at
-// kTicketBytes per ticket, and strictly ordered tickets are as fast as anything
-// tried with more queues and smaller tiles (0.6826 vs 0.6824 ms).
-constexpr int kMaxQueues = 16;
-constexpr unsigned kQueuesHandOver = 4;
-constexpr unsigned kTicketBytesHandOver = 64 * 1024;
-
-struct KParams {
-    void* buf[BLINK_MAX_RANKS];
-    const StageTmpl* tmpl;
-    const StageInst* inst;
-    unsigned long long* done;
-    unsigned long long* ticket;
-    unsigned long long ticket_base[kMaxQueues];  // value of each queue's counter when this call starts
-    unsigned n_queues;
-    unsigned long long n_items;
-    unsigned long long static_items;  // tickets below this are dealt round-robin, without the counter
-    unsigned long long epoch;
-    unsigned tiles_per_chunk;
-    unsigned tile_shift;  // a tile is 2^tile_shift elements
-    unsigned redop;       // blink_redop_t
-    unsigned group;  // consecutive instances whose tiles are handed out in turn (1 = instance by instance)
-};
-
-// Address spaces: the kernel arguments and the schedule tables are never
-// written by the kernel, so they are read through the constant address space,
-// which lets wave-uniform reads use the scalar unit.
-#define BLINK_CONST __attribute__((address_space(4)))
-using ConstParams = const BLINK_CONST KParams*;
-using ConstTmpl = const BLINK_CONST StageTmpl*;
-using ConstInst = const BLINK_CONST StageInst*;
-
-typedef float F4 __attribute__((ext_vector_type(4)));
-typedef unsigned U4 __attribute__((ext_vector_type(4)));  // one 128-bit access, as raw bits
-
-// Element-wise a (+) b on raw bits; `op` is wave-uniform.  fp32 SUM / PROD: one
-// IEEE operation per element (round to nearest even, subnormals kept).  int32
-// SUM / PROD: unsigned arithmetic, i.e. wrap-around modulo 2^32 without
-// signed-overflow UB.  MIN / MAX: signed comparison for int32; for fp32 the
-// bits are mapped to keys whose signed order is the IEEE total order (-0 below
-// +0; the map is its own inverse), so min and max commute bit for bit.
-template <typename T>
-__device__ __forceinline__ unsigned combine1(unsigned op, unsigned a, unsigned b);
-template <>
-__device__ __forceinline__ unsigned combine1<float>(unsigned op, unsigned a, unsigned b) {
-    if (op == BLINK_SUM)
-        return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b));
-    if (op == BLINK_PROD)
-        return __builtin_bit_cast(unsigned, __builtin_bit_cast(float, a) * __builtin_bit_cast(float, b));
-    const int ka = static_cast<int>(a) ^ ((static_cast<int>(a) >> 31) & 0x7fffffff);
-    const int kb = static_cast<int>(b) ^ ((static_cast<int>(b) >> 31) & 0x7fffffff);
-    const int k = op == BLINK_MIN ? min(ka, kb) : max(ka, kb);
-    return static_cast<unsigned>(k ^ ((k >> 31) & 0x7fffffff));
-}
-template <>
-__device__ __forceinline__ unsigned combine1<unsigned>(unsigned op, unsigned a, unsigned b) {
-    if (op == BLINK_SUM) return a + b;
-    if (op == BLINK_PROD) return a * b;
-    const int sa = static_cast<int>(a), sb = static_cast<int>(b);
-    return static_cast<unsigned>(op == BLINK_MIN ? min(sa, sb) : max(sa, sb));
-}
-template <typename T>
-__device__ __forceinline__ U4 combine4(unsigned op, U4 a, U4 b) {
-    if (op == BLINK_SUM) {  // the common case, kept free of per-element selects
-        if constexpr (std::is_same<T, float>::value)
-            return __builtin_bit_cast(U4, __builtin_bit_cast(F4, a) + __builtin_bit_cast(F4, b));
-        else
-            return a + b;
-    }
-    U4 r;
-    r.x = combine1<T>(op, a.x, b.x);
-    r.y = combine1<T>(op, a.y, b.y);
-    r.z = combine1<T>(op, a.z, b.z);
-    r.w = combine1<T>(op, a.w, b.w);
-    return r;
-}
-
-// Byte `field_offset + i` of a stage template, fetched as part of a 32-bit word
-// so that the scalar unit can do it.
-__device__ __forceinline__ unsigned tmpl_byte(ConstTmpl st, unsigned byte_index) {
-    const BLINK_CONST uint32_t* w = reinterpret_cast<const BLINK_CONST uint32_t*>(st);
-    return (w[byte_index >> 2] >> ((byte_index & 3u) * 8u)) & 0xffu;
-}
-#define BLINK_TMPL(st, field, i) tmpl_byte(st, static_cast<unsigned>(offsetof(StageTmpl, field)) + (i))
-
-// Rank buffers are accessed through buffer descriptors that cover exactly the
-// bytes still to be processed: lanes past the end read zeros and their stores
-// are dropped by the hardware range check, so ragged ends need no branches.
-// The cache-policy bits of each access are chosen per kernel flavour (below).
-constexpr int kRawDword3 = 0x00020000;  // raw 32-bit data format, no swizzle (gfx9 family)
-constexpr int kPolicyDefault = 0;
-constexpr int kPolicyStream = 2;        // nt: streamed once, do not keep in cache
-constexpr int kPolicyThrough = 16;      // sc1: agent scope, stores written through
-constexpr int kPolicySystem = 17;       // sc0 sc1: bypass / write through every cache level
-
-// Kernel flavours: the cache policy of rank-buffer loads and stores.
-enum Flavour : int {
-    kHandOver = 0,    // stages hand chunks over to one another (see blink_consume)
-    kBalanced = 1,    // streaming, about as many bytes read as written
-    kWriteHeavy = 2,  // streaming, at least twice as many bytes written as read
-    kReadHeavy = 3,   // streaming, at least twice as many bytes read as written
-};
-// Measured on 8 x 256 MiB, fp32 (load policy, store policy -> ms):
-//   AllReduce  (nt, nt) 0.676  (nt, nt sc1) 0.668  (default, nt sc1) 0.688  (nt, sc1) 0.676
-//   Reduce     (nt, nt) 0.411  (nt, sc1) 0.383     (default, any) 0.44-0.46
-//   Broadcast  (nt, nt) 0.383  (default, nt sc1) 0.297  (default, nt) 0.304
-//   per-edge AllReduce  (sc0 sc1, sc0 sc1) 1.417  (sc0 sc1 nt, sc0 sc1) 1.337  nt on stores 1.65-1.72
-template <int FLAVOUR>
-struct Policy {
-    static constexpr int kLoad = FLAVOUR == kHandOver ? (kPolicySystem | kPolicyStream)
-                                 : (FLAVOUR == kWriteHeavy ? kPolicyDefault : kPolicyStream);
-    static constexpr int kStore = FLAVOUR == kHandOver     ? kPolicySystem
-                                  : FLAVOUR == kWriteHeavy ? (kPolicyStream | kPolicyThrough)
-                                  : FLAVOUR == kReadHeavy  ? kPolicyThrough
-                                                           : kPolicyStream;
-};
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t rank_window(ConstParams p, unsigned rank,
-                                                              unsigned long long byte_off, unsigned bytes) {
-    char* base = reinterpret_cast<char*>(reinterpret_cast<unsigned long long>(p->buf[rank]) + byte_off);
-    return __builtin_amdgcn_make_buffer_rsrc(base, 0, static_cast<int>(bytes), kRawDword3);
-}
-
-// Phases 1-3 over `bytes` bytes (a multiple of 16) at byte_off for a stage that
-// reads N ranks, U columns per lane and sub-tile.
-template <typename T, int N, int U, int LD, int ST>
-__device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                        unsigned long long byte_off, unsigned bytes, int lane) {
-    constexpr unsigned kSubBytes = kLanes * U * 16;
-    const unsigned redop = p->redop;
-    const int n_op = BLINK_TMPL(st, n_op, 0);
-    const int n_store = BLINK_TMPL(st, n_store, 0);
-    for (unsigned b = 0; b < bytes; b += kSubBytes) {
-        const unsigned left = bytes - b;
-        // phase 1: issue every load, then park the values in LDS
-        U4 r[N][U];
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off + b, left);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                r[i][u] = __builtin_amdgcn_raw_buffer_load_b128(win, (u * kLanes + lane) * 16, 0, LD);
-        }
-#pragma unroll
-        for (int i = 0; i < N; ++i)
-#pragma unroll
-            for (int u = 0; u < U; ++u) slots[(i * U + u) * kLanes + lane] = r[i][u];
-        // phase 2: the stage's micro-program
-        U4 acc[U];
-        for (int o = 0; o < n_op; ++o) {
-            const unsigned code = BLINK_TMPL(st, op, o);
-            U4* sl = slots + (code & 63u) * (U * kLanes) + lane;
-            const unsigned kind = code >> 6;
-            if (kind == OP_LD) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
-            } else if (kind == OP_ADD) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] = combine4<T>(redop, acc[u], sl[u * kLanes]);
-            } else {
-#pragma unroll
-                for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
-            }
-        }
-        // phase 3: stores
-        for (int j = 0; j < n_store; ++j) {
-            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off + b, left);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                __builtin_amdgcn_raw_buffer_store_b128(acc[u], win, (u * kLanes + lane) * 16, 0, ST);
-        }
-    }
-}
-
-// Pick U for a stage that reads N ranks: the largest power of two (at most 16)
-// with N * U <= COLS that does not exceed the tile (cols = tile columns per lane).
-template <typename T, int N, int COLS, int LD, int ST>
-__device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                          unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
-    constexpr int kFit = COLS / N;
-    constexpr int kBudget = kFit >= 16 ? 16 : (kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1)));
-    if constexpr (kBudget >= 16)
-        if (cols >= 16) return run_vec<T, N, 16, LD, ST>(slots, p, st, byte_off, bytes, lane);
-    if constexpr (kBudget >= 8)
-        if (cols >= 8) return run_vec<T, N, 8, LD, ST>(slots, p, st, byte_off, bytes, lane);
-    if constexpr (kBudget >= 4)
-        if (cols >= 4) return run_vec<T, N, 4, LD, ST>(slots, p, st, byte_off, bytes, lane);
-    if constexpr (kBudget >= 2)
-        if (cols >= 2) return run_vec<T, N, 2, LD, ST>(slots, p, st, byte_off, bytes, lane);
-    run_vec<T, N, 1, LD, ST>(slots, p, st, byte_off, bytes, lane);
-}
-
-template <typename T, int COLS, int LD, int ST>
-__device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                            unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
-    switch (BLINK_TMPL(st, n_load, 0)) {
-#define BLINK_CASE(N) case N: run_vec_n<T, N, COLS, LD, ST>(slots, p, st, byte_off, bytes, cols, lane); break;
-        BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
-        BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
-        BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
-#undef BLINK_CASE
-        default: break;
-    }
-}
-
-// The same for up to kLanes single 4-byte elements: the ragged end of a payload
-// whose length is not a multiple of 4 elements, and chunks that do not start on
-// a 16-byte boundary.  Slow path; one element per lane.
-template <typename T, int LD, int ST>
-__device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstParams p, ConstTmpl st,
-                                           unsigned long long byte_off, unsigned bytes, int lane) {
-    const int n_load = BLINK_TMPL(st, n_load, 0);
-    for (int i = 0; i < n_load; ++i) {
-        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off, bytes);
-        slots[i * kLanes + lane] = __builtin_amdgcn_raw_buffer_load_b32(win, lane * 4, 0, LD);
-    }
-    unsigned acc = 0;
-    const unsigned redop = p->redop;
-    const int n_op = BLINK_TMPL(st, n_op, 0);
-    for (int o = 0; o < n_op; ++o) {
-        const unsigned code = BLINK_TMPL(st, op, o);
-        unsigned* sl = slots + (code & 63u) * kLanes + lane;
-        const unsigned kind = code >> 6;
-        if (kind == OP_LD)
-            acc = *sl;
-        else if (kind == OP_ADD)
-            acc = combine1<T>(redop, acc, *sl);
-        else
-            *sl = acc;
-    }
-    const int n_store = BLINK_TMPL(st, n_store, 0);
-    for (int j = 0; j < n_store; ++j) {
-        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off, bytes);
-        __builtin_amdgcn_raw_buffer_store_b32(acc, win, lane * 4, 0, ST);
-    }
-}
-
-// T: element type (float, or unsigned for wrap-around int32).  FLAVOUR selects
-// how data is exchanged between stages:
-//   streaming flavours: the schedule has no stage that waits for another (TREE
-//          fusion): streaming accesses with the policy measured best for the
-//          schedule's mix of reads and writes, no fences;
-//   kHandOver: stages hand chunks over to each other, possibly across XCDs whose
-//          L2 caches are not coherent with one another: all rank-buffer accesses
-//          use system-scope cache policy (loads bypass, stores write through;
-//          the loads also carry the streaming hint, which changes no scope),
-//          so the hand-over needs no L2 write-back or invalidate, only "my
-//          stores have completed" before the counter is bumped.
-// COLS: the column budget (LDS slots per lane).
-// The by-value argument is only there to size the kernel-argument segment; it is
-// read through the constant address space (see ConstParams).
-template <typename T, int FLAVOUR, int COLS>
-__global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
-    __shared__ U4 slots[COLS * kLanes];  // 16 or 32 KiB: COLS columns per lane
-    constexpr int LD = Policy<FLAVOUR>::kLoad;
-    constexpr int ST = Policy<FLAVOUR>::kStore;
-    const int lane = threadIdx.x;
-    ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
-    unsigned long long* const ticket = p->ticket;
-    unsigned long long* const done = p->done;
-    ConstTmpl const tmpl = reinterpret_cast<ConstTmpl>(reinterpret_cast<unsigned long long>(p->tmpl));
-    ConstInst const inst = reinterpret_cast<ConstInst>(reinterpret_cast<unsigned long long>(p->inst));
-    const unsigned long long n_items = p->n_items, epoch = p->epoch;
-    const unsigned n_queues = p->n_queues;
-    const unsigned tiles_per_chunk = p->tiles_per_chunk;
-    const unsigned tile_shift = p->tile_shift;
-    const unsigned tile_elems = 1u << tile_shift;
-    const unsigned cols = min(tile_elems / kMinTile, static_cast<unsigned>(COLS));
-    const unsigned group = p->group;
-    const unsigned n_inst = static_cast<unsigned>(n_items / tiles_per_chunk);
-
-    // The loop has exactly one lane-dependent region, at its head: the compiler
-    // must never get the chance to let some lanes run ahead of lane 0 around
-    // the loop (readfirstlane needs lane 0 present).  Hence the completion
-    // signal of a tile is posted together with the next ticket draw; every
-    // other branch, the back edges included, is wave-uniform.
-    //
-    // Small schedules without dependencies are dealt round-robin instead (wave w
-    // takes tickets w, w + grid, ...; static_items == n_items): even several
-    // counters are too slow when thousands of waves each want one small tile.
-    //
-    // Drawn tickets: ticket static_items + j * n_queues + q is the j-th of queue
-    // q.  A wave starts on queue (its number mod n_queues), stays with it until
-    // it is empty and then goes round the others, so every wave draws exactly
-    // one ticket past the end of every queue.  The grid has at least n_queues
-    // waves, so each queue has waves of its own; with dependencies this keeps
-    // the schedule free of deadlock: take the first unfinished ticket t in
-    // schedule order.  Everything it waits for is finished.  If t is drawn its
-    // holder runs; if not, its queue is not empty, the queue's own waves hold
-    // only earlier tickets of that queue, which are finished, so one of them
-    // draws t next.
-    const unsigned long long static_items = p->static_items;
-    unsigned long long next_static = blockIdx.x;
-    unsigned queue = blockIdx.x % n_queues, empty_queues = 0;
-    long long pending = -1;  // instance whose finished tile still has to be counted
-    for (;;) {
-        unsigned long long t;
-        if (next_static < static_items) {
-            t = next_static;
-            next_static += gridDim.x;
-        } else {
-            if (static_items == n_items) break;  // fully dealt out: nothing left to draw
-            unsigned long long raw = 0;
-            if (lane == 0) {
-                if (pending >= 0)
-                    __hip_atomic_fetch_add(done + pending * kCounterStride, 1ull, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                raw = __hip_atomic_fetch_add(ticket + queue * kCounterStride, 1ull, __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
-            }
-            pending = -1;
-            const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw));
-            const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw >> 32));
-            const unsigned long long nth = ((static_cast<unsigned long long>(hi) << 32) | lo) - p->ticket_base[queue];
-            t = static_items + nth * n_queues + queue;
-            if (t >= n_items) {  // this queue is empty: on to the next, or done
-                if (++empty_queues == n_queues) break;
-                queue = queue + 1 == n_queues ? 0 : queue + 1;
-                continue;
-            }
-        }
-        if (t >= n_items) break;
-        // ticket -> (instance, tile).  Within a group of `group` consecutive
-        // instances (the trees' turns at one chunk position) tickets walk tile
-        // by tile across the instances, so neighbouring waves work on all trees
-        // at once (section 4.2.2); group == 1 keeps an instance's tiles together.
-        const unsigned long long per_group = static_cast<unsigned long long>(group) * tiles_per_chunk;
-        const unsigned first = static_cast<unsigned>(t / per_group) * group;
-        const unsigned members = min(group, n_inst - first);
-        const unsigned within = static_cast<unsigned>(t - static_cast<unsigned long long>(first) * tiles_per_chunk);
-        const unsigned ii = first + within % members;
-        const unsigned tile = within / members;
-        ConstInst in = inst + ii;
-        // Tiles lie on the absolute grid of tile_elems-element blocks of the
-        // payload, so tile starts are 128-byte (indeed tile-size) aligned even
-        // when a tree's share starts at an odd multiple of 16 bytes; the first
-        // and last tile of an instance are the ragged ones.
-        const unsigned long long off = in->off, end = off + in->len;
-        const unsigned long long block = (off >> tile_shift) + tile;
-        const unsigned long long lo_e = max(off, block << tile_shift);
-        const unsigned long long hi_e = min(end, (block + 1) << tile_shift);
-        if (lo_e < hi_e) {  // instances have at most tiles_per_chunk tiles, some fewer
-            const unsigned tlen = static_cast<unsigned>(hi_e - lo_e);
-            ConstTmpl st = tmpl + in->tmpl;
-
-            const int n_dep = in->n_dep;
-            if (n_dep) {
-                if (lane < n_dep) {
-                    const unsigned long long want =
-                        epoch * (((end + tile_elems - 1) >> tile_shift) - (off >> tile_shift));
-                    const unsigned long long* f = done + static_cast<long long>(in->dep[lane]) * kCounterStride;
-                    // poll, backing off up to ~2 us between looks so that waiting
-                    // waves leave the memory system to the working ones
-                    int naps = 1;
-                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
-                        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
-                        if (naps < 8) naps *= 2;
-                    }
-                }
-                // orders the polls before the data loads; the loads themselves bypass the caches
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            }
-
-            const unsigned long long e0 = lo_e;  // first element of the tile
-            if ((e0 & 3ull) == 0) {
-                const unsigned vec_bytes = (tlen >> 2) * 16u;
-                if (vec_bytes) run_vec_any<T, COLS, LD, ST>(slots, p, st, e0 * 4ull, vec_bytes, cols, lane);
-                const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
-                if (rem)
-                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + vec_bytes,
-                                          rem * 4u, lane);
-            } else {
-                // chunk size not a multiple of 4 elements: element-wise, slow but correct
-                for (unsigned b = 0; b < tlen * 4u; b += kLanes * 4u)
-                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + b,
-                                          min(static_cast<unsigned>(kLanes) * 4u, tlen * 4u - b), lane);
-            }
-
-            if (BLINK_TMPL(st, signals, 0)) {
-                // every store of this wave has reached memory before the counter moves
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                __builtin_amdgcn_s_waitcnt(0);
-                pending = ii;
-            }
-        }
-    }
-}
 
 // ---- host side ------------------------------------------------------------------------
 namespace {
@@ -466,24 +16,9 @@ namespace {
         }                                                                                 \
     } while (0)
 
-using KernelFn = void (*)(const KParams);
-
-template <typename T, int COLS>
-KernelFn pick_kernel_of(int flavour) {
-    switch (flavour) {
-        case kHandOver: return blink_consume<T, kHandOver, COLS>;
-        case kWriteHeavy: return blink_consume<T, kWriteHeavy, COLS>;
-        case kReadHeavy: return blink_consume<T, kReadHeavy, COLS>;
-        default: return blink_consume<T, kBalanced, COLS>;
-    }
-}
-
 KernelFn pick_kernel(blink_dtype_t dtype, int flavour, bool many_waves) {
-    if (dtype == BLINK_FP32)
-        return many_waves ? pick_kernel_of<float, kColumnsMany>(flavour)
-                          : pick_kernel_of<float, kColumnsStream>(flavour);
-    return many_waves ? pick_kernel_of<unsigned, kColumnsMany>(flavour)
-                      : pick_kernel_of<unsigned, kColumnsStream>(flavour);
+    if (dtype == BLINK_FP32) return many_waves ? kernel_f32_many(flavour) : kernel_f32_stream(flavour);
+    return many_waves ? kernel_i32_many(flavour) : kernel_i32_stream(flavour);
 }
 
 // kMaxQueues ticket counters, then one counter per stage instance, all kCounterStride words apart

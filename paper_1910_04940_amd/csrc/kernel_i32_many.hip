@@ -1,0 +1,8 @@
+// Instantiations of the kernel: int32 elements (added as unsigned: wrap-around), 16 columns per lane.  See kernel.hpp.
+#include "kernel.hpp"
+
+namespace blink {
+
+KernelFn kernel_i32_many(int flavour) { return pick_kernel_of<unsigned, kColumnsMany>(flavour); }
+
+}  // namespace blink
