@@ -224,8 +224,10 @@ void blink_schedule_free(blink_schedule_t* s);
  *              the order fixed by the tree that owns j (int32: modulo 2^32);
  *   broadcast: every rank = the root's buffer.
  * k, n_elems and the collective must be those the schedule was made for
- * (BLINK_EMISMATCH otherwise).  The first call on a schedule also allocates
- * and fills its small device-side tables (synchronously). */
+ * (BLINK_EMISMATCH otherwise).  With n_elems == 0 the call does nothing and
+ * does not look at the entries of bufs (they may be null).  The first call
+ * on a schedule also allocates and fills its small device-side tables
+ * (synchronously). */
 blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                                blink_schedule_t* s, void* stream);
 blink_status_t blink_broadcast(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,

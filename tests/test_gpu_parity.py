@@ -212,6 +212,7 @@ def test_empty_payload_is_a_no_op(dev):
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 0, 64)
     bufs = [torch.zeros(4, device=dev) for _ in range(4)]
     bl.blink_allreduce(bufs, 0, bl.BLINK_FP32, sched, stream())
+    bl.blink_allreduce([0, 0, 0, 0], 0, bl.BLINK_FP32, sched, stream())   # null pointers are not looked at
     torch.cuda.synchronize()
 
 
