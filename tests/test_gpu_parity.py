@@ -181,6 +181,39 @@ def test_uneven_weights(dev):
             assert_fp32_close_and_equal(b.cpu().numpy(), want[0], f"uneven weights fusion {fusion}")
 
 
+# The paper's micro-benchmark shapes (section 2.2): depth (chains) and breadth
+# (fan-in / fan-out up to 3) are among TOPOLOGIES; here the two with several
+# flows through one node.  Ranks 0 and 1 send, 2 is the centre, 3 and 4 receive.
+PAPER_SHAPES = {
+    # two trees through the centre: both inputs are folded at rank 2, one tree
+    # delivers to rank 3 first, the other to rank 4 first
+    "multi-input multi-output": ([3, 4], [(2, 2, 3, -1, 3), (2, 2, 4, 4, -1)], [1.0, 1.0]),
+    # two reduce-and-forward chains 0 -> 1 -> 2 and 4 -> 3 -> 2 merging at the centre
+    "multi-chain aggregation": ([2], [(1, 2, -1, 2, 3)], [1.0]),
+    # fan-in and fan-out of three at one node
+    "fan of three": ([0], [(-1, 0, 0, 0, 1)], [1.0]),
+}
+
+
+@pytest.mark.parametrize("shape", PAPER_SHAPES)
+@pytest.mark.parametrize("fusion", FUSIONS)
+@pytest.mark.parametrize("dtype", ["int32", "fp32"])
+def test_micro_benchmark_tree_shapes_of_the_paper(dev, shape, fusion, dtype):
+    roots, parents, w = PAPER_SHAPES[shape]
+    trees = bl.blink_trees_from_arrays(5, roots, parents, w)
+    n, chunk = 250_003, 16_384
+    x = [si.payload(61, r, n, "int" if dtype == "int32" else "uniform", dtype) for r in range(5)]
+    want = ox.tree_order_allreduce(x, roots, parents, w)
+    if dtype == "int32":
+        assert np.array_equal(want, ox.allreduce_int32_definition(x))
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    bl.blink_allreduce(bufs, n, bl.BLINK_INT32 if dtype == "int32" else bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert b.cpu().numpy().tobytes() == want.tobytes(), shape
+
+
 # ---- Broadcast -----------------------------------------------------------------------
 @pytest.mark.parametrize("top,root", [(si.hybrid_cube_mesh(), 0), (si.complete_graph(4), 2),
                                       (si.chain(6), 5), (si.hybrid_cube_mesh(doubled=True), 3)])
