@@ -128,9 +128,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     }
     // A few waves per CU, each with 32 KiB of loads in flight, saturate HBM;
     // more waves only add ticket and polling traffic.  Measured best: 2, and 3
-    // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms)
-    // or where stages wait for one another.
-    int per_cu = std::min(cached, read_heavy || s.has_deps ? 3 : 2);
+    // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms),
+    // where stages wait for one another, or where a stage reads more than 8
+    // ranks (only 2 columns per rank fit then; 12 ranks: 5.14 -> 5.43 TB/s).
+    int per_cu = std::min(cached, read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2);
     if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
     if (h->wide && h->wg_per_cu == 0) per_cu = cached;
     const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
