@@ -419,3 +419,29 @@ def test_gather_collects_at_the_root(dev, top, root, fusion):
     # nobody's own piece is disturbed
     for r in range(k):
         assert np.array_equal(bufs[r][r * m:(r + 1) * m].cpu().numpy(), x[r][r * m:(r + 1) * m])
+
+
+# ---- many hand-overs ---------------------------------------------------------------
+@pytest.mark.parametrize("fusion", [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE])
+def test_many_hand_overs_between_waves_stay_exact(dev, fusion):
+    """Small chunks on a deep tree: tens of thousands of chunk hand-overs between
+    waves on different XCDs per call, 60 calls in a row on one schedule.  int32,
+    so every element has a closed form: the sum times k^(calls-1) modulo 2^32."""
+    top = si.chain(8)
+    n, chunk, k = 1 << 21, 1 << 10, 8
+    trees = pack(top, 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    assert sched.num_stages >= 2048 * 8
+    x = [si.hash_payload(17, r, 0, n, "int32") for r in range(k)]
+    bufs = to_dev(x, dev)
+    first = ox.allreduce_int32_definition(x).view(np.uint32).astype(np.uint64)
+    calls = 0
+    for burst in (1, 9, 20, 30):
+        for _ in range(burst):
+            bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream())
+        calls += burst
+        torch.cuda.synchronize()
+        want = (first * np.uint64(pow(k, calls - 1, 1 << 32))) & np.uint64(0xFFFFFFFF)
+        for r in (0, 3, 7):
+            got = bufs[r].cpu().numpy().view(np.uint32).astype(np.uint64)
+            assert np.array_equal(got, want), f"after {calls} calls, rank {r}"
