@@ -69,3 +69,30 @@ def test_repeated_calls_and_a_large_payload_on_two_full_servers(dev):
     twice = ox.allreduce_int32_definition([once] * 16)
     for b in bufs:
         assert np.array_equal(b.cpu().numpy(), twice)
+
+
+def test_two_tree_sets_on_a_split_payload(dev):
+    """Section 3.4 end to end: one set of trees per class of links (here a chain
+    standing in for the slow class, the packed cube-mesh trees for the fast one),
+    the payload cut where blink_hybrid_split says, each part reduced along its
+    own trees by a call on offset pointers."""
+    n, chunk, k = 3_000_000, 1 << 16, 8
+    d_slow, d_fast = bl.blink_hybrid_split(n * 4.0, 10e9, 100e9, 20e-6)
+    want_slow, _ = om.hybrid_split(n * 4.0, 10e9, 100e9, 20e-6)
+    assert d_slow == pytest.approx(want_slow) and d_slow + d_fast == pytest.approx(n * 4.0)
+    cut = int(d_slow // 16) * 4                       # elements, on a 16-byte boundary
+    assert 0 < cut < n
+    slow_top, fast_top = si.chain(8), si.hybrid_cube_mesh()
+    slow = bl.blink_pack_trees(k, slow_top.src, slow_top.dst, slow_top.cap, 0)
+    fast = bl.blink_pack_trees(k, fast_top.src, fast_top.dst, fast_top.cap, 0)
+    x = [si.payload(24, r, n, "uniform", "fp32") for r in range(k)]
+    bufs = to_dev(x, dev)
+    s1 = bl.blink_make_schedule(slow, bl.BLINK_OP_ALLREDUCE, cut, chunk, bl.BLINK_FUSE_TREE)
+    s2 = bl.blink_make_schedule(fast, bl.BLINK_OP_ALLREDUCE, n - cut, chunk, bl.BLINK_FUSE_TREE)
+    bl.blink_allreduce([b[:cut] for b in bufs], cut, bl.BLINK_FP32, s1, stream())
+    bl.blink_allreduce([b[cut:] for b in bufs], n - cut, bl.BLINK_FP32, s2, stream())
+    torch.cuda.synchronize()
+    want = np.concatenate([ox.tree_order_allreduce([a[:cut] for a in x], *slow.as_lists()),
+                           ox.tree_order_allreduce([a[cut:] for a in x], *fast.as_lists())])
+    for r, b in enumerate(bufs):
+        assert_fp32_close_and_equal(b.cpu().numpy(), want, f"rank {r}")
