@@ -4,6 +4,8 @@
 
 namespace blink {
 
+constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
+
 // ---- host side ------------------------------------------------------------------------
 namespace {
 
@@ -109,7 +111,15 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     }
     const uint64_t write_bytes = s.traffic_bytes - s.read_bytes;
     const bool read_heavy = s.read_bytes >= 2 * write_bytes, write_heavy = write_bytes >= 2 * s.read_bytes;
-    const int flavour = s.has_deps ? kHandOver : (read_heavy ? kReadHeavy : (write_heavy ? kWriteHeavy : kBalanced));
+    // Rank buffers that together fit the memory-side cache (256 MiB) are written
+    // without the streaming hint: whoever reads the result next (here: the next
+    // call) finds it there (8 x 16 MiB: 62 -> 45 us per call; no change from
+    // 8 x 64 MiB on, and a loss at 8 x 256 MiB).  That is the read-heavy policy.
+    const bool fits_cache = static_cast<uint64_t>(k) * n * 4 <= kMemorySideCacheBytes;
+    const int flavour = s.has_deps   ? kHandOver
+                        : write_heavy ? kWriteHeavy
+                        : (read_heavy || fits_cache) ? kReadHeavy
+                                                     : kBalanced;
     KernelFn fn = pick_kernel(dtype, flavour, h->wide);
     int& cached = h->occupancy[dtype == BLINK_FP32];
     if (cached == 0) {
