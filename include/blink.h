@@ -116,6 +116,29 @@ typedef struct {
     uint64_t len;    /* elements */
 } blink_step_t;
 
+/* One pass of the kernel over a chunk ("stage"): what blink_schedule_get_stages
+ * reports, so that a schedule can be checked, or replayed on the host, without
+ * a GPU.  For every element of [off, off + len): slot i <- rank load_rank[i]
+ * (i < n_load); then the n_op micro-operations in order, each (kind << 6) | slot
+ * with kind 0: acc <- slot, 1: acc <- acc (+) slot, 2: slot <- acc; finally acc
+ * is stored to every rank in store_rank[0 .. n_store).  deps: indices of the
+ * earlier stages all of which must have finished on their whole chunk first. */
+#define BLINK_STAGE_MAX_OPS 40
+#define BLINK_STAGE_MAX_DEPS 8
+typedef struct {
+    uint64_t off;
+    uint32_t len;
+    int32_t tree;    /* the packed tree the stage belongs to */
+    int32_t chunk;   /* chunk index inside its flow's range */
+    int32_t flow;    /* one tree carrying one contiguous range in one direction;
+                        the gathers have several per tree (one per piece) */
+    uint8_t n_load, n_op, n_store, n_dep;
+    uint8_t load_rank[BLINK_MAX_RANKS];
+    uint8_t store_rank[BLINK_MAX_RANKS];
+    uint8_t op[BLINK_STAGE_MAX_OPS];
+    int32_t deps[BLINK_STAGE_MAX_DEPS];
+} blink_stage_t;
+
 /* ---- tree packing (host only; no GPU needed) ------------------------------ */
 
 /* Pack spanning trees into a capacitated directed graph (section 3.1): k
@@ -203,6 +226,9 @@ size_t blink_schedule_num_stages(const blink_schedule_t* s);  /* passes the kern
 int blink_schedule_num_trees(const blink_schedule_t* s);
 /* out[num_steps] (host, caller-allocated): the step list in execution order. */
 blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t* out);
+/* out[num_stages] (host, caller-allocated): the kernel's passes in the order
+ * in which their tickets are handed out (a topological order of the deps). */
+blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_t* out);
 /* out[T+1] (host): share boundaries b_0 = 0 .. b_T = n_elems. */
 blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out);
 /* Bytes the kernel reads plus writes in rank buffers for one call with 4-byte

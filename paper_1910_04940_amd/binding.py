@@ -31,6 +31,12 @@ STEP_DTYPE = np.dtype([("kind", "<i4"), ("tree", "<i4"), ("chunk", "<i4"), ("src
                        ("dst", "<i4"), ("n_deps", "<i4"), ("deps", "<i4", (2,)),
                        ("off", "<u8"), ("len", "<u8")], align=True)
 
+# numpy mirror of blink_stage_t
+STAGE_DTYPE = np.dtype([("off", "<u8"), ("len", "<u4"), ("tree", "<i4"), ("chunk", "<i4"), ("flow", "<i4"),
+                        ("n_load", "u1"), ("n_op", "u1"), ("n_store", "u1"), ("n_dep", "u1"),
+                        ("load_rank", "u1", (16,)), ("store_rank", "u1", (16,)), ("op", "u1", (40,)),
+                        ("deps", "<i4", (8,))], align=True)
+
 EXPORTS = [
     "blink_pack_trees", "blink_trees_from_arrays", "blink_trees_count", "blink_trees_k",
     "blink_trees_rate", "blink_trees_get", "blink_trees_free", "blink_make_schedule",
@@ -40,6 +46,7 @@ EXPORTS = [
     "blink_allreduce_op", "blink_reduce", "blink_allgather", "blink_gather", "blink_strerror",
     "blink_miad_create", "blink_miad_chunk", "blink_miad_steady", "blink_miad_report",
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
+    "blink_schedule_get_stages",
 ]
 
 
@@ -104,6 +111,7 @@ def lib() -> C.CDLL:
     L.blink_hybrid_split.argtypes = [C.c_double] * 4 + [C.POINTER(C.c_double)] * 2
     L.blink_schedule_num_steps.argtypes = [vp]
     L.blink_schedule_num_steps.restype = C.c_size_t
+    L.blink_schedule_get_stages.argtypes = [vp, vp]
     L.blink_schedule_num_stages.argtypes = [vp]
     L.blink_schedule_num_stages.restype = C.c_size_t
     L.blink_schedule_num_trees.argtypes = [vp]
@@ -244,6 +252,11 @@ class Schedule:
     def steps(self) -> np.ndarray:
         out = np.zeros(self.num_steps, STEP_DTYPE)
         _check(lib().blink_schedule_get_steps(self._h, out.ctypes.data), "blink_schedule_get_steps")
+        return out
+
+    def stages(self) -> np.ndarray:
+        out = np.zeros(self.num_stages, STAGE_DTYPE)
+        _check(lib().blink_schedule_get_stages(self._h, out.ctypes.data), "blink_schedule_get_stages")
         return out
 
     def bounds(self) -> List[int]:

@@ -151,6 +151,32 @@ blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t*
     return BLINK_OK;
 }
 
+blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_t* out) {
+    static_assert(BLINK_STAGE_MAX_OPS == blink::kMaxOps && BLINK_STAGE_MAX_DEPS == blink::kMaxDeps,
+                  "the public stage record mirrors the internal one");
+    if (!s || (!out && !s->s.inst.empty())) return BLINK_EINVAL;
+    for (size_t i = 0; i < s->s.inst.size(); ++i) {
+        const blink::StageInst& in = s->s.inst[i];
+        const blink::StageTmpl& st = s->s.tmpl[in.tmpl];
+        blink_stage_t& o = out[i];
+        std::memset(&o, 0, sizeof o);
+        o.off = in.off;
+        o.len = in.len;
+        o.tree = s->s.inst_where[i].tree;
+        o.chunk = s->s.inst_where[i].chunk;
+        o.flow = s->s.inst_where[i].flow;
+        o.n_load = st.n_load;
+        o.n_op = st.n_op;
+        o.n_store = st.n_store;
+        o.n_dep = static_cast<uint8_t>(in.n_dep);
+        std::memcpy(o.load_rank, st.load_rank, sizeof o.load_rank);
+        std::memcpy(o.store_rank, st.store_rank, sizeof o.store_rank);
+        std::memcpy(o.op, st.op, sizeof o.op);
+        for (int d = 0; d < BLINK_STAGE_MAX_DEPS; ++d) o.deps[d] = d < static_cast<int>(in.n_dep) ? in.dep[d] : -1;
+    }
+    return BLINK_OK;
+}
+
 blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out) {
     if (!s || !out) return BLINK_EINVAL;
     for (size_t i = 0; i < s->s.bounds.size(); ++i) out[i] = s->s.bounds[i];

@@ -258,7 +258,7 @@ struct Flow {
 struct Built {
     std::vector<StageTmpl> tmpl;
     std::vector<StageInst> inst;
-    std::vector<std::pair<int, int>> where;  // per instance: (tree, chunk)
+    std::vector<InstWhere> where;  // per instance: tree, chunk, flow
 };
 
 // Lay the stages of all flows and chunks out in execution order.  A stage of
@@ -312,7 +312,7 @@ Built instantiate(const std::vector<std::vector<StageTmpl>>& per_flow, const std
         for (int d = 0; d < kMaxDeps; ++d) in.dep[d] = -1;
         for (int d = 0; d < st.n_dep; ++d)
             in.dep[d] = pos[key.flow][key.chunk_idx * per_flow[key.flow].size() + st.dep_local[d]];
-        b.where[i] = {fl.tree, static_cast<int>(key.chunk_idx)};
+        b.where[i] = {fl.tree, static_cast<int>(key.chunk_idx), key.flow};
     }
     return b;
 }
@@ -384,8 +384,8 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
         const StageTmpl& st = e.tmpl[in.tmpl];
         blink_step_t& s = out.steps[i];
         s.kind = st.n_load == 2 ? BLINK_STEP_REDUCE : BLINK_STEP_COPY;
-        s.tree = e.where[i].first;
-        s.chunk = e.where[i].second;
+        s.tree = e.where[i].tree;
+        s.chunk = e.where[i].chunk;
         s.src = st.n_load == 2 ? st.load_rank[1] : st.load_rank[0];
         s.dst = st.store_rank[0];
         s.n_deps = in.n_dep;
@@ -397,10 +397,12 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
     if (fusion == BLINK_FUSE_EDGE) {
         out.tmpl = std::move(e.tmpl);
         out.inst = std::move(e.inst);
+        out.inst_where = std::move(e.where);
     } else {
         Built f = instantiate(fused, ff, chunk);
         out.tmpl = std::move(f.tmpl);
         out.inst = std::move(f.inst);
+        out.inst_where = std::move(f.where);
     }
     out.max_slots = 1;
     out.traffic_bytes = 0;

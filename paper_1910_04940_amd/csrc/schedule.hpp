@@ -41,6 +41,13 @@ struct StageInst {
 };
 static_assert(sizeof(StageTmpl) % 4 == 0, "StageTmpl is read as 32-bit words");
 
+// Where a stage instance belongs: the packed tree, the chunk inside the flow's
+// range, and the flow (one tree carrying one contiguous range in one direction;
+// the gathers have several flows per tree).
+struct InstWhere {
+    int tree, chunk, flow;
+};
+
 struct Schedule {
     int k = 0;
     int n_trees = 0;
@@ -52,6 +59,7 @@ struct Schedule {
     std::vector<blink_step_t> steps;     // public tree-edge step list, execution order
     std::vector<StageTmpl> tmpl;
     std::vector<StageInst> inst;         // execution (ticket) order; dependencies point backwards
+    std::vector<InstWhere> inst_where;   // per instance: what it belongs to
     uint32_t max_slots = 1;              // largest n_load
     bool has_deps = false;               // some stage waits for another
     uint64_t traffic_bytes = 0;          // bytes read plus written in rank buffers per call
