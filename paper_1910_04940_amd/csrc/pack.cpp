@@ -14,10 +14,15 @@
 // Section 3.2.1 (fewer trees): weights restricted to unit*{0,1,2,..} over the
 // MWU trees, total weight maximised by depth-first branch and bound; unit = 1
 // first (the paper's 0/1 program, a multiplicity standing for repeated trees),
-// halved until the rate is within prune_tol of the MWU rate.  If no grid down
-// to 1/8 gets there within the node budget, the heaviest MWU trees whose
-// weights add up to (1 - prune_tol) of the MWU rate are kept instead (dropping
-// trees never violates a capacity).
+// halved until the rate is within prune_tol of the MWU rate (only grids that
+// the capacities themselves lie on are tried).  If no grid down to 1/8 gets
+// there within the node budget (capacities that are not multiples of a common
+// unit), the weights are re-optimised as a linear program over the
+// MWU trees, max sum w subject to the arc capacities: a vertex of that
+// polytope has at most as many positive weights as there are arcs, and its
+// rate is at least MWU's.  The lightest trees are then dropped one at a time,
+// the program re-solved over the rest, while the rate stays within prune_tol
+// of the MWU rate (the paper's "relax until within the threshold").
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -264,6 +269,134 @@ struct GridSearch {
     }
 };
 
+// max sum_j x_j  subject to  sum_j [arc i in tree j] x_j <= cap_i,  x >= 0, by
+// the simplex method on a dense tableau (slack basis to start from: the origin
+// is feasible).  cols[j] lists the arcs of column j.  Returns a vertex solution
+// (hence at most cap.size() positive entries); false if the iteration limit
+// was hit.  Dantzig's rule, switching to Bland's after a run of degenerate
+// pivots so that it cannot cycle.
+bool solve_packing_lp(const std::vector<double>& cap, const std::vector<const std::vector<int>*>& cols,
+                      std::vector<double>& x) {
+    const int m = static_cast<int>(cap.size()), n = static_cast<int>(cols.size());
+    const int width = n + m + 1;  // tree columns, slack columns, right-hand side
+    std::vector<double> t(static_cast<size_t>(m + 1) * width, 0.0);
+    auto at = [&](int r, int c) -> double& { return t[static_cast<size_t>(r) * width + c]; };
+    for (int j = 0; j < n; ++j) {
+        for (int a : *cols[j]) at(a, j) = 1.0;
+        at(m, j) = -1.0;  // objective row holds the negated reduced costs
+    }
+    for (int i = 0; i < m; ++i) {
+        at(i, n + i) = 1.0;
+        at(i, width - 1) = cap[i];
+    }
+    std::vector<int> basis(m);
+    for (int i = 0; i < m; ++i) basis[i] = n + i;
+    const double tol = 1e-11;
+    int degenerate_run = 0;
+    const long limit = 200L * (m + 10);
+    for (long it = 0; it < limit; ++it) {
+        int enter = -1;
+        if (degenerate_run < 2 * m) {
+            double most = -1e-9;
+            for (int j = 0; j < n + m; ++j)
+                if (at(m, j) < most) {
+                    most = at(m, j);
+                    enter = j;
+                }
+        } else {
+            for (int j = 0; j < n + m && enter < 0; ++j)
+                if (at(m, j) < -1e-9) enter = j;
+        }
+        if (enter < 0) {  // optimal
+            x.assign(n, 0.0);
+            for (int i = 0; i < m; ++i)
+                if (basis[i] < n) x[basis[i]] = std::max(0.0, at(i, width - 1));
+            return true;
+        }
+        int leave = -1;
+        double best_ratio = std::numeric_limits<double>::infinity();
+        for (int i = 0; i < m; ++i) {
+            const double a = at(i, enter);
+            if (a <= tol) continue;
+            const double ratio = at(i, width - 1) / a;
+            if (ratio < best_ratio - 1e-12 || (ratio < best_ratio + 1e-12 && leave >= 0 && basis[i] < basis[leave])) {
+                best_ratio = ratio;
+                leave = i;
+            }
+        }
+        if (leave < 0) return false;  // unbounded: cannot happen, every tree uses an arc
+        degenerate_run = best_ratio <= 1e-12 ? degenerate_run + 1 : 0;
+        const double pivot = at(leave, enter);
+        for (int c = 0; c < width; ++c) at(leave, c) /= pivot;
+        for (int r = 0; r <= m; ++r) {
+            if (r == leave) continue;
+            const double f = at(r, enter);
+            if (f == 0.0) continue;
+            for (int c = 0; c < width; ++c) at(r, c) -= f * at(leave, c);
+        }
+        basis[leave] = enter;
+    }
+    return false;
+}
+
+// The linear-program fallback of section 3.2.1 (see the file header): weights
+// for `cands`, at most one positive weight per arc, rate >= target if possible.
+bool prune_by_lp(const Graph& g, const std::vector<Candidate>& cands, double target, std::vector<double>& w) {
+    std::vector<double> cap;
+    for (const Arc& a : g.arcs) cap.push_back(a.cap);
+    std::vector<int> support(cands.size());
+    for (size_t i = 0; i < cands.size(); ++i) support[i] = static_cast<int>(i);
+    auto solve = [&](const std::vector<int>& idx, std::vector<double>& x) {
+        std::vector<const std::vector<int>*> cols;
+        for (int i : idx) cols.push_back(&cands[i].arcs);
+        return solve_packing_lp(cap, cols, x);
+    };
+    std::vector<double> x;
+    if (!solve(support, x)) return false;
+    auto shrink = [&](std::vector<int>& idx, std::vector<double>& val) {  // keep the positive entries
+        std::vector<int> i2;
+        std::vector<double> v2;
+        for (size_t j = 0; j < idx.size(); ++j)
+            if (val[j] > 1e-9) {
+                i2.push_back(idx[j]);
+                v2.push_back(val[j]);
+            }
+        idx.swap(i2);
+        val.swap(v2);
+    };
+    shrink(support, x);
+    // drop light trees while the re-optimised rate stays above the target
+    for (bool dropped = true; dropped && support.size() > 1;) {
+        dropped = false;
+        std::vector<size_t> order(support.size());
+        for (size_t j = 0; j < order.size(); ++j) order[j] = j;
+        std::sort(order.begin(), order.end(), [&](size_t a, size_t b) { return x[a] < x[b]; });
+        for (size_t victim : order) {
+            std::vector<int> rest;
+            for (size_t j = 0; j < support.size(); ++j)
+                if (j != victim) rest.push_back(support[j]);
+            std::vector<double> y;
+            if (!solve(rest, y)) continue;
+            double rate = 0.0;
+            for (double v : y) rate += v;
+            if (rate >= target - 1e-9) {
+                support.swap(rest);
+                x.swap(y);
+                shrink(support, x);
+                dropped = true;
+                break;
+            }
+        }
+    }
+    w.assign(cands.size(), 0.0);
+    double rate = 0.0;
+    for (size_t j = 0; j < support.size(); ++j) {
+        w[support[j]] = x[j];
+        rate += x[j];
+    }
+    return rate >= target - 1e-9;
+}
+
 void emit(const std::vector<Candidate>& cands, const std::vector<double>& w, int k, int root, Trees& out) {
     out.k = k;
     for (size_t i = 0; i < cands.size(); ++i) {
@@ -339,6 +472,10 @@ blink_status_t pack_trees(int k, int m, const int32_t* src, const int32_t* dst, 
     const double target = (1.0 - prune_tol) * mwu_rate;
 
     for (double unit = 1.0; unit >= 0.125; unit *= 0.5) {
+        // a grid can only reach the optimum if the capacities lie on it
+        bool on_grid = true;
+        for (const Arc& a : g.arcs) on_grid = on_grid && std::fabs(a.cap / unit - std::round(a.cap / unit)) < 1e-9;
+        if (!on_grid) continue;
         GridSearch gs(g, root, cands, unit, 2000000);
         gs.descend(0, 0);
         if (gs.best * unit >= target - 1e-9) {
@@ -348,7 +485,21 @@ blink_status_t pack_trees(int k, int m, const int32_t* src, const int32_t* dst, 
             return BLINK_OK;
         }
     }
-    // keep the heaviest MWU trees up to the tolerated loss
+    {
+        std::vector<double> w;
+        if (prune_by_lp(g, cands, target, w)) {
+            // guard against rounding: scale down if an arc came out a hair over capacity
+            std::vector<double> load(g.arcs.size(), 0.0);
+            for (size_t i = 0; i < cands.size(); ++i)
+                for (int a : cands[i].arcs) load[a] += w[i];
+            double congestion = 1.0;
+            for (size_t a = 0; a < load.size(); ++a) congestion = std::max(congestion, load[a] / g.arcs[a].cap);
+            for (double& v : w) v /= congestion;
+            emit(cands, w, k, root, out);
+            return BLINK_OK;
+        }
+    }
+    // last resort: keep the heaviest MWU trees up to the tolerated loss
     std::vector<double> w(cands.size(), 0.0);
     double kept = 0.0;
     for (size_t i = 0; i < cands.size() && kept < target; ++i) {

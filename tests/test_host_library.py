@@ -78,6 +78,29 @@ def test_random_fractional_graphs_feasible_and_near_optimal(seed):
     rate = op.check_packing(g, roots, parents, w)
     assert rate <= lam + 1e-9
     assert rate >= (1 - tol) * (1 - 2 * eps) * lam
+    # a vertex of the packing polytope over MWU's trees: at most one tree per arc
+    assert trees.count <= g.m
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_fractional_capacities_still_give_few_trees(seed):
+    """Capacities on no common grid: MWU spreads the rate over thousands of trees;
+    what comes back must be a handful (never more than there are arcs) at a rate
+    within the tolerance."""
+    k = 4 + seed % 13
+    top = si.random_digraph(k, 0.3 + 0.05 * (seed % 8), 4000 + seed, int_caps=False)
+    g = og.Digraph.from_topology(top)
+    try:
+        trees = pack(top, 0)
+    except bl.BlinkError as e:
+        assert e.status == bl.BLINK_EDISCONNECTED
+        return
+    roots, parents, w = trees.as_lists()
+    rate = op.check_packing(g, roots, parents, w)
+    assert trees.count <= min(g.m, 40)
+    if k <= 12:
+        lam = og.min_root_cut(g, 0)
+        assert (1 - 0.05) * (1 - 2 * 0.05) * lam <= rate <= lam + 1e-9
 
 
 @pytest.mark.parametrize("seed", range(80))
