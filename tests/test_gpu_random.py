@@ -46,3 +46,25 @@ def test_random_trees_on_the_gpu(dev, seed):
     for t, r in enumerate(roots):
         for v in (range(k) if op == bl.BLINK_OP_ALLREDUCE else [r]):
             assert got[v][b[t]:b[t + 1]].tobytes() == want[b[t]:b[t + 1]].tobytes(), (t, v)
+
+
+@pytest.mark.parametrize("seed", [2, 6, 16, 24, 34])
+@pytest.mark.parametrize("fusion", [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE])
+def test_many_unevenly_weighted_trees_from_real_valued_capacities(dev, seed, fusion):
+    """Random digraphs with real-valued capacities: the packer returns a dozen or
+    more trees with uneven weights, hence many flows with ragged shares."""
+    k = 8 + seed % 9
+    top = si.random_digraph(k, 0.5, 4000 + seed, int_caps=False)
+    trees = bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, 0)
+    roots, parents, w = trees.as_lists()
+    assert trees.count >= 8
+    n, chunk = 400_003, 9_000
+    x = [si.payload(seed, r, n, "uniform", "fp32") for r in range(k)]
+    want = ox.tree_order_allreduce(x, roots, parents, w)
+    bufs = to_dev(x, dev)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    print(f"seed {seed}: k={k} T={trees.count} fusion={fusion}", flush=True)
+    bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream())
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert b.cpu().numpy().tobytes() == want.tobytes()
