@@ -181,7 +181,9 @@ void blink_trees_free(blink_trees_t* trees);
  * dependencies, ordered so that all
  * trees advance together, one chunk of each in turn (section 4.2.2).
  * A node folds its children in ascending rank id (this fixes the fp32
- * association order).  Broadcast needs all trees to share one root, else
+ * association order).  The reduce phase uses every tree arc backwards: like the
+ * paper (section 3.3) this takes links to be bidirectional; no topology is
+ * consulted here.  Broadcast needs all trees to share one root, else
  * BLINK_EMISMATCH.  n_elems == 0 gives an empty, valid schedule. */
 blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, size_t n_elems,
                                    size_t chunk_elems, blink_fusion_t fusion,
