@@ -6,10 +6,10 @@
 //
 // A workgroup is ONE 64-lane wavefront: nothing in the kernel needs a
 // workgroup barrier, and a wave that waits for a dependency holds up nobody
-// else.  Work unit: (stage instance, tile).  Waves draw units from one ticket
-// counter in the schedule's execution order, so every unit a wave might have
-// to wait for has already been drawn by a wave that is running: waiting can
-// never deadlock, whatever the grid size.
+// else.  Work unit: (stage instance, tile).  Waves draw units from ticket
+// counters in the schedule's execution order, so every unit a wave might have
+// to wait for has already been drawn by a running wave, or is about to be (see
+// the kernel's loop): waiting can never deadlock, whatever the grid size.
 //
 // A tile (256..65536 elements, chosen per schedule) is cut into sub-tiles; a
 // sub-tile of a stage is processed in three phases by the 64 lanes, each owning
