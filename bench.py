@@ -47,7 +47,6 @@ def parse():
     ap.add_argument("--separate-buffers", action="store_true",
                     help="one allocation per rank buffer instead (whatever distances the allocator gives)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--check", action="store_true", help="verify sampled outputs against the oracle")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark, run a plain device copy of known size "
                          "(reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
@@ -232,7 +231,7 @@ def main():
         "roofline": roofline,
     }
 
-    if args.check or not args.no_cpu_baseline:
+    if not args.no_cpu_baseline:
         # leave the device with exactly one AllReduce applied to the pristine inputs
         restore()
         step()
