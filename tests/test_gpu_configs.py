@@ -226,3 +226,28 @@ def test_int32_hand_over_kernels_at_streaming_size(dev, fusion):
     torch.cuda.synchronize()
     for b in bufs:
         assert np.array_equal(b.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("fusion", ["tree", "edge"])
+def test_more_than_2_to_the_32_elements_per_rank(dev, fusion):
+    """Offsets beyond 32 bits: 2 ranks of 2^32 + 12,291 int32 each (34 GiB on the
+    device), ragged end included.  Inputs are generated where they live; the
+    oracle recomputes sampled slices from the same counter-based recipe."""
+    n, chunk, k = (1 << 32) + 12_291, 1 << 20, 2
+    top = si.complete_graph(2)
+    trees = pack(top, 1)
+    bufs = [si.hash_payload_torch(13, r, n, "int32", dev) for r in range(k)]
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, FUSION[fusion])
+    assert sched.num_steps == 2 * ((n + chunk - 1) // chunk)
+    bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(bufs[0], bufs[1])
+    width = 8192
+    starts = [0, (1 << 31) - width // 2, (1 << 32) - width, (1 << 32) - width // 2, 1 << 32, n - width, n - 5]
+    starts += [int(s) for s in np.random.default_rng(6).integers(0, n - width, 16)]
+    for a in starts:
+        m = min(width, n - a)
+        xs = [si.hash_payload(13, r, a, m, "int32") for r in range(k)]
+        want = ox.allreduce_int32_definition(xs)
+        got = bufs[0][a:a + m].cpu().numpy()
+        assert np.array_equal(got, want), f"slice at {a}"
