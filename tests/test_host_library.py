@@ -272,6 +272,23 @@ def test_schedule_error_codes():
     assert empty.num_steps == 0 and empty.num_stages == 0 and empty.traffic_bytes == 0
 
 
+def test_chunk_lengths_at_the_32_bit_limit():
+    """A chunk's length travels in 32 bits.  A chunk size beyond that is fine as
+    long as no share is that long (it then means "one chunk per tree"), an error
+    otherwise; payloads beyond 2^32 elements work with ordinary chunks."""
+    trees = pack(si.complete_graph(4), 0)
+    one = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 1000, 1 << 40, bl.BLINK_FUSE_EDGE)
+    assert one.num_steps == 3 * 6                       # one chunk per tree
+    with pytest.raises(bl.BlinkError) as e:
+        bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 1 << 33, 1 << 33)
+    assert e.value.status == bl.BLINK_EINVAL
+    big = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, (1 << 33) + 5, 1 << 28, bl.BLINK_FUSE_TREE)
+    assert big.bounds()[-1] == (1 << 33) + 5
+    steps = big.steps()
+    assert int(steps["off"].max()) + int(steps["len"][np.argmax(steps["off"])]) == (1 << 33) + 5
+    assert int(steps["len"].astype(np.uint64).sum()) == 3 * ((1 << 33) + 5)      # 3 arcs per tree
+
+
 # ---- Gather and AllGather -----------------------------------------------------------------
 GATHER_SCHED_CASES = [
     (si.hybrid_cube_mesh(), 0, 8 * 10_001, 3000),
