@@ -92,6 +92,7 @@ struct KParams {
     unsigned tile_shift;  // a tile is 2^tile_shift elements
     unsigned redop;       // blink_redop_t
     unsigned group;  // consecutive instances whose tiles are handed out in turn (1 = instance by instance)
+    unsigned max_naps;  // longest pause between two looks at a dependency, in units of ~0.2 us
 };
 
 // Address spaces: the kernel arguments and the schedule tables are never
@@ -421,12 +422,14 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
                     const unsigned long long want =
                         epoch * (((end + tile_elems - 1) >> tile_shift) - (off >> tile_shift));
                     const unsigned long long* f = done + static_cast<long long>(in->dep[lane]) * kCounterStride;
-                    // poll, backing off up to ~2 us between looks so that waiting
-                    // waves leave the memory system to the working ones
-                    int naps = 1;
+                    // poll, backing off (up to ~2 us between looks for large
+                    // schedules) so that waiting waves leave the memory system
+                    // to the working ones
+                    const unsigned max_naps = p->max_naps;
+                    unsigned naps = 1;
                     while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
-                        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
-                        if (naps < 8) naps *= 2;
+                        for (unsigned i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
+                        if (naps < max_naps) naps *= 2;
                     }
                 }
                 // orders the polls before the data loads; the loads themselves bypass the caches
