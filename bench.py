@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--fusion", choices=["edge", "node", "tree"], default="tree")
+    ap.add_argument("--collective", choices=["allreduce", "broadcast"], default="allreduce",
+                    help="broadcast (from rank 0) is the second benchmark configuration; use it with "
+                         "--elems 16777216 for its 64 MiB payload")
     ap.add_argument("--chunk-bytes", type=int, default=1 << 20)
     ap.add_argument("--elems", type=int, default=1 << 26, help="fp32 elements per rank")
     ap.add_argument("--dtype", choices=["fp32", "int32"], default="fp32")
@@ -86,16 +89,17 @@ def traffic_from_profiles(name):
     return None
 
 
-def cpu_baseline(roots, parents, weights, k, n, chunk):
+def cpu_baseline(roots, parents, weights, k, n, chunk, collective):
     """The oracle as it stands, timed on the host: literal step-list execution
-    in NumPy float32 over the full headline workload (one pass)."""
+    in NumPy float32 over the full workload (one pass)."""
     import numpy as np
 
     import synth_inputs as si
     from oracle import execute as ox
     from oracle import schedule as osch
 
-    steps = osch.make_steps(roots, parents, weights, osch.ALLREDUCE, n, chunk)
+    steps = osch.make_steps(roots, parents, weights,
+                            osch.ALLREDUCE if collective == "allreduce" else osch.BROADCAST, n, chunk)
     bufs = [si.payload(0, r, n, "uniform", "fp32") for r in range(k)]
     t0 = time.perf_counter()
     ox.run_steps(bufs, steps)
@@ -134,7 +138,9 @@ def main():
 
     trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
     roots, parents, weights = trees.as_lists()
-    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    broadcast = args.collective == "broadcast"
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST if broadcast else bl.BLINK_OP_ALLREDUCE,
+                                   n, chunk, fusion)
     if args.tile_elems or args.wg_per_cu:
         sched.set_launch(args.wg_per_cu, args.tile_elems)
 
@@ -162,7 +168,10 @@ def main():
             b.copy_(p)
 
     def step():
-        bl.blink_allreduce(bufs, n, dtype, sched, stream.cuda_stream)
+        if broadcast:
+            bl.blink_broadcast(bufs, n, dtype, sched, stream.cuda_stream)
+        else:
+            bl.blink_allreduce(bufs, n, dtype, sched, stream.cuda_stream)
 
     since_restore = 0
     for _ in range(args.warmup):
@@ -197,20 +206,23 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = n * 4 / (ms_per_step * 1e-3) / 1e9
 
-    per_elem = {"edge": 20 * (k - 1), "node": None, "tree": 8 * k}[args.fusion]
+    per_elem = ({"edge": 8 * (k - 1), "node": None, "tree": 4 * k} if broadcast else
+                {"edge": 20 * (k - 1), "node": None, "tree": 8 * k})[args.fusion]
     alg_bytes = sched.traffic_bytes          # == per_elem * n for edge and tree
     if per_elem is not None:
         assert alg_bytes == per_elem * n
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
-    prof_name = f"blink_consume_allreduce_cube8_256MiB_{args.fusion}.txt"
+    prof_name = f"blink_consume_{args.collective}_cube8_{n * 4 >> 20}MiB_{args.fusion}.txt"
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS,
-                "traffic": traffic_from_profiles(prof_name) if n == 1 << 26 else None,
+                "traffic": traffic_from_profiles(prof_name),
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "bytes_per_element": alg_bytes / n,
-                "accounting": {"edge": "per-edge: every tree edge is a transfer between two rank buffers, 20(k-1) B/elt",
+                "accounting": {"edge": "per-edge: every tree edge is a transfer between two rank buffers, "
+                                       "20(k-1) B/elt (broadcast: 8(k-1))",
                                "node": "per-node: one pass per fan-in and per fan-out",
-                               "tree": "staged minimum: every rank buffer read once and written once, 8k B/elt"}[args.fusion],
+                               "tree": "staged minimum: every rank buffer read once and written once, 8k B/elt "
+                                       "(broadcast: the root read once, the others written once, 4k)"}[args.fusion],
                 "kernel": "blink_consume", "avg_kernel_ms": avg_kernel_ms,
                 "median_kernel_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
                 "min_kernel_ms": min(kernel_ms)}
@@ -222,7 +234,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.dtype == "fp32" else "i32",
         "data": "synthetic",
-        "config": {"workload": "AllReduce, 8 virtual ranks (HBM buffers on one GPU), unit-capacity hybrid "
+        "config": {"workload": ("Broadcast from rank 0" if broadcast else "AllReduce") +
+                               ", 8 virtual ranks (HBM buffers on one GPU), unit-capacity hybrid "
                                "cube-mesh, root 0, 4 packed unit trees, "
                                f"{n} {args.dtype} per rank, {args.chunk_bytes} B chunks, uniform[-1,1] seed 0",
                    "ranks": k, "elements_per_rank": n, "chunk_bytes": args.chunk_bytes,
@@ -232,12 +245,12 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        # leave the device with exactly one AllReduce applied to the pristine inputs
+        # leave the device with exactly one call applied to the pristine inputs
         restore()
         step()
         torch.cuda.synchronize()
     if not args.no_cpu_baseline and args.dtype == "fp32":
-        base, want = cpu_baseline(roots, parents, weights, k, n, chunk)
+        base, want = cpu_baseline(roots, parents, weights, k, n, chunk, args.collective)
         out["cpu_baseline"] = base
         got = bufs[k - 1].cpu().numpy()
         same = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
