@@ -26,7 +26,9 @@
  *     passes in; the library never frees or reallocates caller memory.
  *   - A schedule keeps device-side progress counters: it may be used by many
  *     calls one after another on ONE stream at a time.  Two calls that overlap
- *     in time on the same schedule race.  Every launch carries the number of
+ *     in time on the same schedule race (stages of one may then wait for
+ *     progress the other consumed; such a wait is bounded, see
+ *     blink_schedule_status).  Every launch carries the number of
  *     the call on its schedule, so a call must not be recorded into a HIP graph
  *     (a replay would repeat a number); the first call on a schedule also
  *     allocates, which a capturing stream forbids anyway.
@@ -54,7 +56,8 @@ typedef enum {
     BLINK_EDISCONNECTED = 2, /* some vertex cannot be reached from the root: rate 0 */
     BLINK_ENOMEM = 3,        /* host or device allocation failed */
     BLINK_EMISMATCH = 4,     /* schedule does not fit the call (k, n, collective) */
-    BLINK_EHIP = 5           /* a HIP runtime call failed (no device, launch error) */
+    BLINK_EHIP = 5,          /* a HIP runtime call failed (no device, launch error) */
+    BLINK_ESTUCK = 6         /* a stage gave up waiting for another one (see blink_schedule_status) */
 } blink_status_t;
 
 typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
@@ -64,11 +67,11 @@ typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
 /* ALLGATHER and GATHER work on buffers of n_elems = k * m elements in which rank
  * j owns piece j = [j*m, (j+1)*m) and starts with it in place: afterwards every
  * rank (ALLGATHER) or the root of each tree (GATHER, on that tree's share of
- * every piece) holds all k pieces.  "Gather is the inverse of Broadcast, and
- * AllGather is AllReduce without a reduction": every piece is split among the
- * trees by weight; a tree moves its share of piece j hop by hop along its own
- * edges, away from rank j in every direction (ALLGATHER) or up to its root
- * (GATHER). */
+ * every piece) holds all k pieces.  Section 4.1 derives both from the
+ * collectives above: a gather runs a broadcast backwards, an all-gather is an
+ * all-reduce that only moves data.  Here every piece is split among the trees
+ * by weight; a tree moves its share of piece j hop by hop along its own edges,
+ * away from rank j in every direction (ALLGATHER) or up to its root (GATHER). */
 typedef enum {
     BLINK_OP_BROADCAST = 0, BLINK_OP_ALLREDUCE = 1, BLINK_OP_REDUCE = 2,
     BLINK_OP_ALLGATHER = 3, BLINK_OP_GATHER = 4
@@ -145,7 +148,10 @@ typedef struct {
  * vertices, m arcs src[i] -> dst[i] of capacity cap[i] > 0 (all three: host
  * arrays of length m; a bidirectional link is two arcs; parallel arcs add up).
  * root in [0,k): multiplicative-weight-update fractional packing of
- * arborescences rooted there (section 3.2, accuracy eps in (0, 0.5]), then
+ * arborescences rooted there (section 3.2, accuracy eps in (0, 0.5]; the
+ * rounds needed grow like m ln m / eps^2, and an eps for which that estimate
+ * exceeds 5e7 (eps of 0.005 or less on 240 arcs, below 0.0015 on 32) is refused
+ * with BLINK_EINVAL instead of running for minutes), then
  * reduced to few trees (section 3.2.1) accepting a rate loss of at most
  * prune_tol in [0,1) against the MWU rate.  root == BLINK_ROOT_ANY: k one-hop
  * trees (section 3.5); needs every arc i->j to be present, else BLINK_EINVAL.
@@ -283,6 +289,38 @@ blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtyp
  * device and restarts the schedule's progress counters.  Applies to later
  * calls on this schedule. */
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
+
+/* What became of the calls made on a schedule so far.  In the per-edge and
+ * per-node programs a stage waits, chunk by chunk, for the stages it depends on
+ * (section 4.1: an event per chunk).  Such a wait is bounded: after the wait
+ * limit (default 5 s) the waiting wavefront records what it waited for and
+ * leaves the kernel, every other wait of that call then ends as well, the
+ * kernel finishes normally, and later calls on the schedule do nothing until
+ * blink_schedule_reset.  The rank buffers of an abandoned call hold partial
+ * results.  Nothing but a bug (or two calls overlapping on one schedule) makes
+ * a wait that long. */
+typedef struct {
+    int32_t state;          /* 0: every call so far ran to completion; 1: a wait was abandoned */
+    int32_t stage;          /* index (blink_schedule_get_stages order) of the stage that gave up; -1 if none */
+    int32_t awaited_stage;  /* the stage it waited for; -1 if none */
+    int32_t reserved;
+    uint64_t seen;          /* finished tiles the awaited stage had counted, over all calls */
+    uint64_t wanted;        /* the count it had to reach */
+    uint64_t call;          /* number of the call on this schedule (1 = first) */
+} blink_progress_t;
+/* Waits for the device (hipDeviceSynchronize), then fills *out (host).
+ * BLINK_OK if state == 0, BLINK_ESTUCK otherwise. */
+blink_status_t blink_schedule_status(blink_schedule_t* s, blink_progress_t* out);
+/* Waits for the device, then clears the progress counters and the status
+ * record: the schedule is as after blink_make_schedule (launch overrides are
+ * kept). */
+blink_status_t blink_schedule_reset(blink_schedule_t* s);
+/* Wait limit in microseconds for later calls (0 = the default). */
+blink_status_t blink_schedule_set_wait_limit(blink_schedule_t* s, uint64_t microseconds);
+/* For tests of the give-up path only: counts one call as made without
+ * launching it.  The stages of the next call then wait for progress that never
+ * comes, the waits run into the limit, and the call ends as described above. */
+blink_status_t blink_schedule_test_skip_call(blink_schedule_t* s);
 
 /* ---- chunk-size selection across iterations (host only) ---------------------- */
 

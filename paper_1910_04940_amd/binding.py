@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libblink.so")
 
 BLINK_MAX_RANKS = 16
 BLINK_ROOT_ANY = -1
-BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP = range(6)
+BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP, BLINK_ESTUCK = range(7)
 BLINK_INT32, BLINK_FP32 = 0, 1
 BLINK_OP_BROADCAST, BLINK_OP_ALLREDUCE, BLINK_OP_REDUCE, BLINK_OP_ALLGATHER, BLINK_OP_GATHER = 0, 1, 2, 3, 4
 BLINK_SUM, BLINK_PROD, BLINK_MIN, BLINK_MAX = 0, 1, 2, 3
@@ -30,6 +30,10 @@ BLINK_FUSE_EDGE, BLINK_FUSE_NODE, BLINK_FUSE_TREE = 0, 1, 2
 STEP_DTYPE = np.dtype([("kind", "<i4"), ("tree", "<i4"), ("chunk", "<i4"), ("src", "<i4"),
                        ("dst", "<i4"), ("n_deps", "<i4"), ("deps", "<i4", (2,)),
                        ("off", "<u8"), ("len", "<u8")], align=True)
+
+# numpy mirror of blink_progress_t
+PROGRESS_DTYPE = np.dtype([("state", "<i4"), ("stage", "<i4"), ("awaited_stage", "<i4"), ("reserved", "<i4"),
+                           ("seen", "<u8"), ("wanted", "<u8"), ("call", "<u8")], align=True)
 
 # numpy mirror of blink_stage_t
 STAGE_DTYPE = np.dtype([("off", "<u8"), ("len", "<u4"), ("tree", "<i4"), ("chunk", "<i4"), ("flow", "<i4"),
@@ -46,7 +50,8 @@ EXPORTS = [
     "blink_allreduce_op", "blink_reduce", "blink_allgather", "blink_gather", "blink_strerror",
     "blink_miad_create", "blink_miad_chunk", "blink_miad_steady", "blink_miad_report",
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
-    "blink_schedule_get_stages",
+    "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
+    "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call",
 ]
 
 
@@ -126,6 +131,10 @@ def lib() -> C.CDLL:
     for name in ("blink_allreduce_op", "blink_reduce"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, C.c_int, vp, vp]
     L.blink_schedule_set_launch.argtypes = [vp, C.c_int, C.c_int]
+    L.blink_schedule_status.argtypes = [vp, vp]
+    L.blink_schedule_reset.argtypes = [vp]
+    L.blink_schedule_set_wait_limit.argtypes = [vp, C.c_uint64]
+    L.blink_schedule_test_skip_call.argtypes = [vp]
     L.blink_miad_create.argtypes = [C.c_size_t, C.c_double, C.c_size_t, C.c_size_t, C.c_size_t,
                                     C.c_double, C.POINTER(vp)]
     L.blink_miad_chunk.argtypes = [vp]
@@ -267,6 +276,23 @@ class Schedule:
 
     def set_launch(self, wg_per_cu: int = 0, tile_elems: int = 0) -> None:
         _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, tile_elems), "blink_schedule_set_launch")
+
+    def status(self) -> Tuple[int, dict]:
+        """(status code, blink_progress_t as a dict); waits for the device."""
+        out = np.zeros(1, PROGRESS_DTYPE)
+        st = lib().blink_schedule_status(self._h, out.ctypes.data)
+        if st not in (BLINK_OK, BLINK_ESTUCK):
+            raise BlinkError(st, "blink_schedule_status")
+        return st, {name: int(out[0][name]) for name in PROGRESS_DTYPE.names}
+
+    def reset(self) -> None:
+        _check(lib().blink_schedule_reset(self._h), "blink_schedule_reset")
+
+    def set_wait_limit(self, microseconds: int) -> None:
+        _check(lib().blink_schedule_set_wait_limit(self._h, microseconds), "blink_schedule_set_wait_limit")
+
+    def test_skip_call(self) -> None:
+        _check(lib().blink_schedule_test_skip_call(self._h), "blink_schedule_test_skip_call")
 
 
 def blink_make_schedule(trees: Trees, op: int, n_elems: int, chunk_elems: int,

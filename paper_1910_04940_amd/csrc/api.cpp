@@ -245,6 +245,32 @@ blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int
     return BLINK_OK;
 }
 
+blink_status_t blink_schedule_status(blink_schedule_t* s, blink_progress_t* out) {
+    if (!s || !out) return BLINK_EINVAL;
+    BLINK_GUARD_BEGIN
+    return blink::read_status(s, out);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_schedule_reset(blink_schedule_t* s) {
+    if (!s) return BLINK_EINVAL;
+    BLINK_GUARD_BEGIN
+    return blink::reset_progress(s);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_schedule_set_wait_limit(blink_schedule_t* s, uint64_t microseconds) {
+    if (!s || microseconds > (1ull << 40)) return BLINK_EINVAL;
+    s->wait_limit_us = microseconds;
+    return BLINK_OK;
+}
+
+blink_status_t blink_schedule_test_skip_call(blink_schedule_t* s) {
+    if (!s) return BLINK_EINVAL;
+    s->epoch += 1;
+    return BLINK_OK;
+}
+
 const char* blink_strerror(blink_status_t st) {
     switch (st) {
         case BLINK_OK: return "ok";
@@ -253,6 +279,7 @@ const char* blink_strerror(blink_status_t st) {
         case BLINK_ENOMEM: return "out of memory";
         case BLINK_EMISMATCH: return "schedule does not match the call";
         case BLINK_EHIP: return "HIP runtime error";
+        case BLINK_ESTUCK: return "a stage gave up waiting for another one";
     }
     return "unknown status";
 }

@@ -1,5 +1,6 @@
-// The launcher of the persistent kernel (see kernel.hpp): device-side tables and
-// counters of a schedule, the choice of tile size, grid and kernel flavour, the launch.
+// The launcher of the persistent kernel (see kernel.hpp): the device block of a
+// schedule (status record, progress counters, tables), the launch plan (tile
+// size, kernel flavour), the launch and its bookkeeping.
 #include "kernel.hpp"
 
 namespace blink {
@@ -23,52 +24,156 @@ KernelFn pick_kernel(blink_dtype_t dtype, int flavour, bool many_waves) {
     return many_waves ? kernel_i32_many(flavour) : kernel_i32_stream(flavour);
 }
 
-// kMaxQueues ticket counters, then one counter per stage instance, all kCounterStride words apart
-size_t counter_bytes(const Schedule& s) {
-    return (s.inst.size() + kMaxQueues) * static_cast<size_t>(kCounterStride) * sizeof(unsigned long long);
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+BlockLayout layout_of(const Schedule& s) {
+    constexpr size_t kLine = static_cast<size_t>(kCounterStride) * sizeof(unsigned long long);
+    BlockLayout l;
+    l.ticket = static_cast<size_t>(kStatusWords) * sizeof(unsigned long long);
+    l.done = l.ticket + kMaxQueues * kLine;
+    l.counters_end = l.done + s.inst.size() * kLine;
+    l.tmpl = round_up(l.counters_end, 256);
+    l.inst = round_up(l.tmpl + s.tmpl.size() * sizeof(StageTmpl), 256);
+    l.bytes = round_up(l.inst + s.inst.size() * sizeof(StageInst), 256);
+    return l;
 }
 
+// Fill a block that lives at `block` on the current device: zero the status
+// record and the counters, copy the tables.  Synchronous.
+blink_status_t fill_block(const Schedule& s, const BlockLayout& l, char* block) {
+    BLINK_HIP(hipMemset(block, 0, l.counters_end));
+    BLINK_HIP(hipMemcpy(block + l.tmpl, s.tmpl.data(), s.tmpl.size() * sizeof(StageTmpl), hipMemcpyHostToDevice));
+    BLINK_HIP(hipMemcpy(block + l.inst, s.inst.data(), s.inst.size() * sizeof(StageInst), hipMemcpyHostToDevice));
+    BLINK_HIP(hipDeviceSynchronize());
+    return BLINK_OK;
+}
+
+// The schedule's own block: one allocation, made at the first call on a device.
+// Nothing is left behind when a step fails.
 blink_status_t upload(blink_schedule* h) {
     int dev = -1;
     BLINK_HIP(hipGetDevice(&dev));
     if (h->device == dev) return BLINK_OK;
-    if (h->device >= 0) return BLINK_EMISMATCH;  // tables live on another device
-    const Schedule& s = h->s;
-    BLINK_HIP(hipMalloc(&h->d_tmpl, s.tmpl.size() * sizeof(StageTmpl)));
-    BLINK_HIP(hipMalloc(&h->d_inst, s.inst.size() * sizeof(StageInst)));
-    BLINK_HIP(hipMalloc(&h->d_counters, counter_bytes(s)));
-    BLINK_HIP(hipMemcpy(h->d_tmpl, s.tmpl.data(), s.tmpl.size() * sizeof(StageTmpl), hipMemcpyHostToDevice));
-    BLINK_HIP(hipMemcpy(h->d_inst, s.inst.data(), s.inst.size() * sizeof(StageInst), hipMemcpyHostToDevice));
-    BLINK_HIP(hipMemset(h->d_counters, 0, counter_bytes(s)));
-    BLINK_HIP(hipDeviceSynchronize());
-    hipDeviceProp_t prop;
-    BLINK_HIP(hipGetDeviceProperties(&prop, dev));
-    h->n_cu = prop.multiProcessorCount;
+    if (h->device >= 0) return BLINK_EMISMATCH;  // the block lives on another device
+    const BlockLayout l = layout_of(h->s);
+    void* block = nullptr;
+    BLINK_HIP(hipMalloc(&block, l.bytes));
+    const blink_status_t st = fill_block(h->s, l, static_cast<char*>(block));
+    if (st != BLINK_OK) {
+        (void)hipFree(block);
+        return st;
+    }
+    h->d_block = block;
     h->device = dev;
+    h->epoch = 0;
+    for (uint64_t& b : h->ticket_base) b = 0;
+    return BLINK_OK;
+}
+
+// Tile size, kernel flavour and ticket count of a schedule on this device.
+//
+// The tile is large enough that a ticket moves about kTicketBytes.  A payload
+// too small to give a streaming grid a few dozen such tickets per CU is
+// latency-bound instead ("wide"): then all the waves that fit are used and the
+// tile shrinks until about every other wave has one.
+blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
+    LaunchPlan& pl = h->plan;
+    if (pl.made) return BLINK_OK;
+    const Schedule& s = h->s;
+    if (h->n_cu == 0) {
+        int dev = -1, n_cu = 0;
+        BLINK_HIP(hipGetDevice(&dev));
+        BLINK_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n_cu < 1) return BLINK_EHIP;
+        h->n_cu = n_cu;
+    }
+    uint64_t work = 0;  // elements x stages
+    for (const StageInst& in : s.inst) work += in.len;
+    const uint64_t bytes_per_elem = std::max<uint64_t>(1, s.traffic_bytes / std::max<uint64_t>(1, work));
+    // the power of two nearest (in ratio) to ticket bytes / bytes_per_elem
+    const uint64_t ticket_bytes = s.has_deps ? kTicketBytesHandOver : kTicketBytes;
+    unsigned tile = kMinTile;
+    while (tile < kMaxTile && 2ull * tile * tile * bytes_per_elem * bytes_per_elem < ticket_bytes * ticket_bytes)
+        tile *= 2;
+    pl.wide = work / tile < 24ull * h->n_cu;
+
+    const uint64_t write_bytes = s.traffic_bytes - s.read_bytes;
+    pl.read_heavy = s.read_bytes >= 2 * write_bytes;
+    const bool write_heavy = write_bytes >= 2 * s.read_bytes;
+    // Rank buffers that together fit the memory-side cache (256 MiB) are written
+    // without the streaming hint: whoever reads the result next (here: the next
+    // call) finds it there (8 x 16 MiB: 62 -> 45 us per call; no change from
+    // 8 x 64 MiB on, and a loss at 8 x 256 MiB).  That is the read-heavy policy.
+    const bool fits_cache = static_cast<uint64_t>(s.k) * s.n * 4 <= kMemorySideCacheBytes;
+    pl.flavour = s.has_deps   ? kHandOver
+                 : write_heavy ? kWriteHeavy
+                 : (pl.read_heavy || fits_cache) ? kReadHeavy
+                                                 : kBalanced;
+    if (pl.wide) {
+        int& occ = h->occupancy[dtype == BLINK_FP32];
+        if (occ == 0) {
+            BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, pick_kernel(dtype, pl.flavour, true), kLanes, 0));
+            if (occ < 1) {
+                occ = 0;
+                return BLINK_EHIP;
+            }
+        }
+        while (tile > kMinTile && work / tile < static_cast<uint64_t>(occ) * h->n_cu / 2) tile /= 2;
+    }
+    if (h->tile_override) tile = h->tile_override;
+    pl.tile_elems = tile;
+    pl.tile_shift = 0;
+    while ((1u << pl.tile_shift) < tile) ++pl.tile_shift;
+    uint64_t tiles_per_chunk = 1;
+    for (const StageInst& in : s.inst)
+        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk,
+                                             ((in.off + in.len + tile - 1) >> pl.tile_shift) - (in.off >> pl.tile_shift));
+    pl.tiles_per_chunk = static_cast<uint32_t>(tiles_per_chunk);
+    pl.n_items = static_cast<uint64_t>(s.inst.size()) * tiles_per_chunk;
+    pl.made = true;
     return BLINK_OK;
 }
 
 }  // namespace
 
-// Forget all progress (used when the tile size changes: counters of earlier
-// calls were counted in other units).  Waits for the device first.
+// Forget all progress and the status record, and let the next call plan its
+// launch afresh (used when the tile size changes: counters of earlier calls were
+// counted in other units; and to recover after a wait was abandoned).  Waits for
+// the device first.
 blink_status_t reset_progress(blink_schedule* h) {
     h->epoch = 0;
     for (uint64_t& b : h->ticket_base) b = 0;
-    h->tile_elems = 0;
-    h->tile_final = false;
+    h->plan = LaunchPlan();
+    h->occupancy[0] = h->occupancy[1] = 0;
     if (h->device < 0) return BLINK_OK;
     BLINK_HIP(hipDeviceSynchronize());
-    BLINK_HIP(hipMemset(h->d_counters, 0, counter_bytes(h->s)));
+    BLINK_HIP(hipMemset(h->d_block, 0, layout_of(h->s).counters_end));
     BLINK_HIP(hipDeviceSynchronize());
     return BLINK_OK;
 }
 
+// Wait for the device, then report what the status record of the block says.
+blink_status_t read_status(blink_schedule* h, blink_progress_t* out) {
+    *out = blink_progress_t{};
+    out->stage = out->awaited_stage = -1;
+    if (h->device < 0) return BLINK_OK;  // never ran: nothing can have gone wrong
+    unsigned long long rec[kStatusWords] = {};
+    BLINK_HIP(hipDeviceSynchronize());
+    BLINK_HIP(hipMemcpy(rec, h->d_block, sizeof rec, hipMemcpyDeviceToHost));
+    out->state = static_cast<int32_t>(rec[kStatusState]);
+    if (rec[kStatusState] == 0) return BLINK_OK;
+    out->stage = static_cast<int32_t>(rec[kStatusStage]);
+    out->awaited_stage = static_cast<int32_t>(rec[kStatusAwaited]);
+    out->seen = rec[kStatusSeen];
+    out->wanted = rec[kStatusWanted];
+    out->call = rec[kStatusCall];
+    return BLINK_ESTUCK;
+}
+
 void release_device_state(blink_schedule* h) {
     if (h->device < 0) return;
-    (void)hipFree(h->d_tmpl);
-    (void)hipFree(h->d_inst);
-    (void)hipFree(h->d_counters);
+    (void)hipFree(h->d_block);
+    h->d_block = nullptr;
     h->device = -1;
 }
 
@@ -90,76 +195,40 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     }
     if (s.inst.empty()) return BLINK_OK;
     if (blink_status_t st = upload(h)) return st;
+    if (blink_status_t st = make_plan(h, dtype)) return st;
+    const LaunchPlan& pl = h->plan;
+    const BlockLayout l = layout_of(s);
+    char* const block = static_cast<char*>(h->d_block);
 
-    // Tile size, fixed at the first call (the progress counters count tiles):
-    // large enough that a ticket moves about kTicketBytes.  A payload too small
-    // to give a streaming grid a few dozen such tickets per CU is latency-bound
-    // instead ("wide"): then all the waves that fit are used and the tile
-    // shrinks until about every other wave has one.
-    uint64_t work = 0;  // elements x stages
-    if (!h->tile_final)
-        for (const StageInst& in : s.inst) work += in.len;
-    if (h->tile_elems == 0) {
-        const uint64_t bytes_per_elem = std::max<uint64_t>(1, s.traffic_bytes / std::max<uint64_t>(1, work));
-        // the power of two nearest (in ratio) to ticket bytes / bytes_per_elem
-        const uint64_t ticket_bytes = s.has_deps ? kTicketBytesHandOver : kTicketBytes;
-        unsigned tile = kMinTile;
-        while (tile < kMaxTile && 2ull * tile * tile * bytes_per_elem * bytes_per_elem < ticket_bytes * ticket_bytes)
-            tile *= 2;
-        h->wide = work / tile < 24ull * h->n_cu;
-        h->tile_elems = tile;
-    }
-    const uint64_t write_bytes = s.traffic_bytes - s.read_bytes;
-    const bool read_heavy = s.read_bytes >= 2 * write_bytes, write_heavy = write_bytes >= 2 * s.read_bytes;
-    // Rank buffers that together fit the memory-side cache (256 MiB) are written
-    // without the streaming hint: whoever reads the result next (here: the next
-    // call) finds it there (8 x 16 MiB: 62 -> 45 us per call; no change from
-    // 8 x 64 MiB on, and a loss at 8 x 256 MiB).  That is the read-heavy policy.
-    const bool fits_cache = static_cast<uint64_t>(k) * n * 4 <= kMemorySideCacheBytes;
-    const int flavour = s.has_deps   ? kHandOver
-                        : write_heavy ? kWriteHeavy
-                        : (read_heavy || fits_cache) ? kReadHeavy
-                                                     : kBalanced;
-    KernelFn fn = pick_kernel(dtype, flavour, h->wide);
-    int& cached = h->occupancy[dtype == BLINK_FP32];
-    if (cached == 0) {
-        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&cached, fn, kLanes, 0));
-        if (cached < 1) {
-            cached = 0;
+    KernelFn fn = pick_kernel(dtype, pl.flavour, pl.wide);
+    int& occ = h->occupancy[dtype == BLINK_FP32];
+    if (occ == 0) {
+        BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, kLanes, 0));
+        if (occ < 1) {
+            occ = 0;
             return BLINK_EHIP;
         }
-    }
-    if (!h->tile_final) {
-        unsigned tile = h->tile_elems;
-        if (h->wide)
-            while (tile > kMinTile && work / tile < static_cast<uint64_t>(cached) * h->n_cu / 2) tile /= 2;
-        h->tile_elems = h->tile_override ? h->tile_override : tile;
-        h->tile_final = true;
     }
     // A few waves per CU, each with 32 KiB of loads in flight, saturate HBM;
     // more waves only add ticket and polling traffic.  Measured best: 2, and 3
     // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms),
     // where stages wait for one another, or where a stage reads more than 8
     // ranks (only 2 columns per rank fit then; 12 ranks: 5.14 -> 5.43 TB/s).
-    int per_cu = std::min(cached, read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2);
-    if (h->wg_per_cu > 0) per_cu = std::min(cached, h->wg_per_cu);
-    if (h->wide && h->wg_per_cu == 0) per_cu = cached;
+    int per_cu = std::min(occ, pl.read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2);
+    if (h->wg_per_cu > 0) per_cu = std::min(occ, h->wg_per_cu);
+    if (pl.wide && h->wg_per_cu == 0) per_cu = occ;
     const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
-    const unsigned tile = h->tile_elems;
-    unsigned tile_shift = 0;
-    while ((1u << tile_shift) < tile) ++tile_shift;
-    uint64_t tiles_per_chunk = 1;
-    for (const StageInst& in : s.inst)
-        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk, ((in.off + in.len + tile - 1) >> tile_shift) - (in.off >> tile_shift));
-    const unsigned long long n_items = static_cast<unsigned long long>(s.inst.size()) * tiles_per_chunk;
+    const unsigned long long n_items = pl.n_items;
     const unsigned long long grid = std::min<unsigned long long>(max_grid, n_items);
 
     KParams p{};
     for (int i = 0; i < k; ++i) p.buf[i] = bufs[i];
-    p.tmpl = static_cast<const StageTmpl*>(h->d_tmpl);
-    p.inst = static_cast<const StageInst*>(h->d_inst);
-    p.done = static_cast<unsigned long long*>(h->d_counters) + kMaxQueues * kCounterStride;
-    p.ticket = static_cast<unsigned long long*>(h->d_counters);
+    p.tmpl = reinterpret_cast<const StageTmpl*>(block + l.tmpl);
+    p.inst = reinterpret_cast<const StageInst*>(block + l.inst);
+    p.done = reinterpret_cast<unsigned long long*>(block + l.done);
+    p.ticket = reinterpret_cast<unsigned long long*>(block + l.ticket);
+    p.status = reinterpret_cast<unsigned long long*>(block);
+    p.wait_ticks = (h->wait_limit_us ? h->wait_limit_us : kDefaultWaitMicroseconds) * kTicksPerMicrosecond;
     const unsigned n_queues =
         static_cast<unsigned>(std::min<unsigned long long>(s.has_deps ? kQueuesHandOver : 1, grid));
     p.n_queues = n_queues;
@@ -173,19 +242,30 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     // a ticket's holder known to be running.
     const unsigned long long static_items = (!s.has_deps && n_items / grid <= 4) ? n_items : 0;
     p.static_items = static_items;
-    p.epoch = ++h->epoch;
-    p.tiles_per_chunk = static_cast<unsigned>(tiles_per_chunk);
-    p.tile_shift = tile_shift;
+    p.epoch = h->epoch + 1;
+    p.tiles_per_chunk = pl.tiles_per_chunk;
+    p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
     // Without dependencies the order of tiles is free: interleave the trees tile by tile.
     p.group = s.has_deps ? 1u : std::min(64u, std::max(1u, s.n_flows));
     // Waiting waves look at their dependency every ~0.2 us in small schedules,
     // where a hand-over is most of the time (16 one-hop trees, 256 elements,
     // per-edge: 47 -> 36 us), and back off to ~0.8 us in large ones.
-    p.max_naps = h->wide ? 1 : 4;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(grid)), dim3(kLanes), 0,
-                       static_cast<hipStream_t>(stream), p);
-    BLINK_HIP(hipGetLastError());
+    p.max_naps = pl.wide ? 1 : 4;
+
+    // The launch's own status decides whether the call counts: an error some
+    // earlier HIP call of this thread left behind is not this launch's, and a
+    // launch that failed must not consume a call number or move the ticket
+    // bases (the next call would wait for tiles that nobody ever counted).
+    void* args[] = {&p};
+    const hipError_t launched = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3(static_cast<unsigned>(grid)),
+                                                dim3(kLanes), args, 0, static_cast<hipStream_t>(stream));
+    if (launched != hipSuccess) {
+        std::fprintf(stderr, "blink: kernel launch failed: %s\n", hipGetErrorString(launched));
+        (void)hipGetLastError();  // the failed launch's error is reported here, not left for later calls
+        return BLINK_EHIP;
+    }
+    h->epoch += 1;
     if (static_items < n_items) {
         // queue q holds the drawn tickets q, q + n_queues, ...; every wave
         // draws exactly one ticket past the end of every queue

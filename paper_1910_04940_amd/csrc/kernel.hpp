@@ -76,6 +76,23 @@ constexpr int kCounterStride = 32;  // in 8-byte words
 constexpr int kMaxQueues = 16;
 constexpr unsigned kQueuesHandOver = 4;
 constexpr unsigned kTicketBytesHandOver = 64 * 1024;
+// The status record at the head of a schedule's device block, 64-bit words.
+// Word kStatusState is 0 while all is well.  A wave whose wait for another stage
+// outlasts the limit makes it 1 (the first such wave wins), fills in the other
+// words and leaves; from then on every wave that looks leaves too, and every
+// later launch on the block returns at once, until the host clears the record.
+enum : int {
+    kStatusState = 0,    // 0 = ok, 1 = a wait was abandoned
+    kStatusStage = 1,    // the stage instance that waited
+    kStatusAwaited = 2,  // the instance it waited for
+    kStatusSeen = 3,     // finished tiles that instance had counted
+    kStatusWanted = 4,   // finished tiles it had to reach
+    kStatusCall = 5,     // number of the call on its schedule
+    kStatusWords = 32,   // the record takes one 256-byte line of its own
+};
+// The steady counter the waits are timed with ticks at 100 MHz.
+constexpr unsigned long long kTicksPerMicrosecond = 100;
+constexpr unsigned long long kDefaultWaitMicroseconds = 5000000;  // 5 s: generous; only a bug waits that long
 
 struct KParams {
     void* buf[BLINK_MAX_RANKS];
@@ -83,6 +100,8 @@ struct KParams {
     const StageInst* inst;
     unsigned long long* done;
     unsigned long long* ticket;
+    unsigned long long* status;          // the status record (kStatus* words)
+    unsigned long long wait_ticks;       // longest wait for another stage, in ticks of the steady counter
     unsigned long long ticket_base[kMaxQueues];  // value of each queue's counter when this call starts
     unsigned n_queues;
     unsigned long long n_items;
@@ -342,11 +361,20 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     const unsigned group = p->group;
     const unsigned n_inst = static_cast<unsigned>(n_items / tiles_per_chunk);
 
-    // The loop has exactly one lane-dependent region, at its head: the compiler
-    // must never get the chance to let some lanes run ahead of lane 0 around
-    // the loop (readfirstlane needs lane 0 present).  Hence the completion
-    // signal of a tile is posted together with the next ticket draw; every
-    // other branch, the back edges included, is wave-uniform.
+    // Lane-dependent regions.  readfirstlane needs lane 0 present, so the
+    // compiler must never get the chance to let some lanes run ahead of lane 0
+    // around the loop: a version with a lane-0 region at the tail of the loop
+    // (completion signal) and one at its head (ticket draw) had the two merged
+    // across the back edge and hung.  Hence the completion signal of a tile is
+    // posted together with the next ticket draw, in ONE lane-0 region at the
+    // head, and the back edges are wave-uniform.  The only other lane-dependent
+    // region is the wait for dependencies in the middle of the body (lanes
+    // below n_dep poll one counter each).  It cannot be merged with the region
+    // at the head in either direction: between the two, on both sides, lies
+    // wave-uniform code with effects of its own (the readfirstlane pair and the
+    // ticket arithmetic after the head; the tile's loads and stores after the
+    // wait), and the wait ends in a ballot over all lanes, which the lanes can
+    // only reach together.  All other branches are wave-uniform.
     //
     // Small schedules without dependencies are dealt round-robin instead (wave w
     // takes tickets w, w + grid, ...; static_items == n_items): even several
@@ -362,6 +390,11 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     // holder runs; if not, its queue is not empty, the queue's own waves hold
     // only earlier tickets of that queue, which are finished, so one of them
     // draws t next.
+    //
+    // A block whose status record is set (an earlier call gave up a wait, so its
+    // counters no longer mean anything) is left alone.
+    unsigned long long* const status = p->status;
+    if (__hip_atomic_load(status + kStatusState, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const unsigned long long static_items = p->static_items;
     unsigned long long next_static = blockIdx.x;
     unsigned queue = blockIdx.x % n_queues, empty_queues = 0;
@@ -418,20 +451,43 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
 
             const int n_dep = in->n_dep;
             if (n_dep) {
+                bool gave_up = false;
                 if (lane < n_dep) {
                     const unsigned long long want =
                         epoch * (((end + tile_elems - 1) >> tile_shift) - (off >> tile_shift));
                     const unsigned long long* f = done + static_cast<long long>(in->dep[lane]) * kCounterStride;
-                    // poll, backing off (up to ~2 us between looks for large
+                    // poll, backing off (up to ~0.8 us between looks for large
                     // schedules) so that waiting waves leave the memory system
-                    // to the working ones
+                    // to the working ones.  Every 64th look also checks the
+                    // clock and the status record: a wait that outlasts the
+                    // limit, or any wait once another wave has given up, ends
+                    // here, and the wave leaves the kernel.
                     const unsigned max_naps = p->max_naps;
-                    unsigned naps = 1;
-                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+                    unsigned naps = 1, looks = 0;
+                    unsigned long long since = 0, seen;
+                    while ((seen = __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) < want) {
                         for (unsigned i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
                         if (naps < max_naps) naps *= 2;
+                        if ((++looks & 63u) != 0) continue;
+                        const unsigned long long now = wall_clock64();
+                        if (since == 0) since = now;
+                        const bool late = now - since > p->wait_ticks;
+                        if (late && __hip_atomic_exchange(status + kStatusState, 1ull, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT) == 0) {
+                            status[kStatusStage] = ii;
+                            status[kStatusAwaited] = static_cast<unsigned long long>(in->dep[lane]);
+                            status[kStatusSeen] = seen;
+                            status[kStatusWanted] = want;
+                            status[kStatusCall] = epoch;
+                        }
+                        if (late || __hip_atomic_load(status + kStatusState, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            gave_up = true;
+                            break;
+                        }
                     }
                 }
+                if (__builtin_amdgcn_ballot_w64(gave_up) != 0) break;  // wave-uniform: leave the kernel
                 // orders the polls before the data loads; the loads themselves bypass the caches
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             }

@@ -165,20 +165,47 @@ ParentVec parents_of(const Graph& g, const std::vector<int>& in_arc, int root) {
     return p;
 }
 
+// Upper estimate of the rounds MWU needs (section 3.2: O(m ln m / eps^2)): every
+// round multiplies the length of some arc by at least 1 + eps on its way from
+// delta / c to at most (1 + eps) / c.
+double mwu_round_estimate(int m, double eps) {
+    return m * std::log((1.0 + eps) * m) / (eps * std::log1p(eps));
+}
+constexpr double kMaxMwuRounds = 5e7;  // about a minute of host time on 240 arcs
+
 // MWU fractional packing; returns distinct trees with feasible weights.
+//
+// The common start value of the arc lengths, delta = (1 + eps) * ((1 + eps) m)^(-1/eps),
+// underflows a double for small eps.  Where it does, `len` holds l_e / delta
+// instead of l_e and the loop ends when log(sum c_e len_e) reaches -log(delta);
+// whenever such relative lengths grow large they are scaled down together (a
+// common factor changes no minimum arborescence) and `log_scale` keeps count.
 std::vector<Candidate> mwu(const Graph& g, int root, double eps) {
     const int m = static_cast<int>(g.arcs.size());
-    const double delta = (1.0 + eps) * std::pow((1.0 + eps) * m, -1.0 / eps);
-    std::vector<double> len(m);
-    double potential = 0.0;  // sum c_e * l_e
-    for (int i = 0; i < m; ++i) {
-        len[i] = delta / g.arcs[i].cap;
-        potential += delta;
+    double log_goal = std::log((1.0 + eps) * m) / eps - std::log1p(eps);  // -log(delta)
+    double start = 1.0, log_scale = 0.0;
+    if (log_goal < 690.0) {  // delta is an ordinary double: work with the lengths themselves
+        start = (1.0 + eps) * std::pow((1.0 + eps) * m, -1.0 / eps);
+        log_goal = 0.0;
     }
+    std::vector<double> len(m);
+    double potential = 0.0;  // sum c_e * len_e
+    for (int i = 0; i < m; ++i) {
+        len[i] = start / g.arcs[i].cap;
+        potential += start;
+    }
+    auto unfinished = [&]() { return std::log(potential) + log_scale < log_goal; };
+    auto rescale = [&]() {
+        if (potential < 0x1p400) return;
+        for (double& l : len) l *= 0x1p-400;
+        potential *= 0x1p-400;
+        log_scale += 400.0 * std::log(2.0);
+    };
     std::map<ParentVec, size_t> seen;
     std::vector<Candidate> out;
     std::vector<int> in_arc;
-    while (potential < 1.0) {
+    while (unfinished()) {
+        rescale();
         min_arborescence(g, root, len, in_arc);
         std::vector<int> arcs;
         double gamma = std::numeric_limits<double>::infinity(), found_len = 0.0;
@@ -205,7 +232,7 @@ std::vector<Candidate> mwu(const Graph& g, int root, double eps) {
                 len[a] = grown;
                 cur_len += grown;
             }
-        } while (potential < 1.0 && cur_len <= (1.0 + eps) * found_len);
+        } while (unfinished() && potential < 0x1p800 && cur_len <= (1.0 + eps) * found_len);
     }
     std::vector<double> load(m, 0.0);
     for (const Candidate& c : out)
@@ -464,6 +491,8 @@ blink_status_t pack_trees(int k, int m, const int32_t* src, const int32_t* dst, 
             if (!seen[v]) return BLINK_EDISCONNECTED;
     }
 
+    // an accuracy that would need more rounds than anybody waits for is refused at once
+    if (mwu_round_estimate(static_cast<int>(g.arcs.size()), eps) > kMaxMwuRounds) return BLINK_EINVAL;
     std::vector<Candidate> cands = mwu(g, root, eps);
     std::sort(cands.begin(), cands.end(),
               [](const Candidate& a, const Candidate& b) { return a.weight > b.weight; });

@@ -1,25 +1,51 @@
-// The schedule handle: host-side schedule plus the device-side tables and
-// progress counters the kernel uses.
+// The schedule handle: host-side schedule, the launch plan derived from it, and
+// the device-side block (status record, progress counters, tables) the kernel uses.
 #pragma once
+#include <cstddef>
 #include <cstdint>
 
 #include "schedule.hpp"
 
+namespace blink {
+
+// What a launch needs besides the schedule itself.  It depends only on the
+// schedule, the device and the caller's overrides, so it is worked out once, at
+// the first call, and kept until an override changes (the progress counters
+// count tiles, so the tile size may not change while they hold progress).
+struct LaunchPlan {
+    bool made = false;
+    bool wide = false;             // small payload: use every wave that fits
+    int flavour = 0;               // cache policy of the kernel (see kernel.hpp)
+    unsigned tile_elems = 0;       // elements per tile
+    unsigned tile_shift = 0;       // log2 of it
+    uint32_t tiles_per_chunk = 1;  // most tiles any stage instance has
+    uint64_t n_items = 0;          // tickets per call
+    bool read_heavy = false;
+};
+
+// Layout of the device block of a schedule, in bytes from its start:
+//   status record (kStatusWords 64-bit words), ticket counters, one counter of
+//   finished tiles per stage instance (counters kCounterStride words apart),
+//   stage templates, stage instances.
+struct BlockLayout {
+    size_t ticket = 0, done = 0, tmpl = 0, inst = 0, bytes = 0;
+    size_t counters_end = 0;  // status record and counters are [0, counters_end)
+};
+
+}  // namespace blink
+
 struct blink_schedule {
     blink::Schedule s;
-    int device = -1;              // HIP device holding the tables; -1 = not uploaded yet
-    void* d_tmpl = nullptr;       // StageTmpl[]
-    void* d_inst = nullptr;       // StageInst[]
-    void* d_counters = nullptr;   // u64 ticket counters, then one u64 of finished tiles per instance
-    uint64_t epoch = 0;           // calls made so far; counters hold epoch * tiles
+    blink::LaunchPlan plan;
+    int device = -1;              // HIP device holding the block; -1 = not uploaded yet
+    void* d_block = nullptr;      // see BlockLayout
+    uint64_t epoch = 0;           // calls made so far on d_block; its counters hold epoch * tiles
     uint64_t ticket_base[16] = {};  // value of each ticket counter when the next call starts
+    uint64_t wait_limit_us = 0;   // longest wait for another stage; 0 = default
     int n_cu = 0;
     int wg_per_cu = 0;            // launch override (0 = automatic)
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
-    unsigned tile_elems = 0;      // elements per tile in use (0 = not chosen yet)
-    bool tile_final = false;      // tile_elems has had its small-payload adjustment
-    bool wide = false;            // small payload: use every wave that fits
-    int occupancy[2] = {0, 0};    // waves per CU, cached per dtype
+    int occupancy[2] = {0, 0};    // waves per CU of the plan's kernel, per dtype
     unsigned last_grid = 0;
 };
 
@@ -27,5 +53,6 @@ namespace blink {
 blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, blink_dtype_t dtype,
                        blink_op_t op, blink_redop_t redop, void* stream);
 blink_status_t reset_progress(blink_schedule* h);
+blink_status_t read_status(blink_schedule* h, blink_progress_t* out);
 void release_device_state(blink_schedule* h);
 }  // namespace blink

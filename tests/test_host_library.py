@@ -165,6 +165,28 @@ def test_pack_error_codes():
     assert "unreachable" in bl.strerror(bl.BLINK_EDISCONNECTED)
 
 
+def test_small_eps_neither_hangs_nor_loses_the_rate():
+    """The start length of section 3.2's arcs, (1+eps)((1+eps)m)^(-1/eps), is below
+    the smallest double for eps of a few thousandths; the packing must still end
+    and reach the min root cut.  An eps that would take tens of millions of rounds
+    is refused at once."""
+    import time
+    top = si.hybrid_cube_mesh()
+    assert (1.004 * len(top.src)) ** (-1 / 0.004) == 0.0          # the underflow in question
+    t0 = time.time()
+    trees = pack(top, 0, eps=0.004)
+    assert time.time() - t0 < 60
+    assert abs(trees.rate - 4.0) < 1e-9 and trees.count == 4
+    roots, parents, w = trees.as_lists()
+    assert op.check_packing(og.Digraph.from_topology(top), roots, parents, w) == 4.0
+    k16 = si.complete_graph(16)
+    t0 = time.time()
+    with pytest.raises(bl.BlinkError) as e:
+        pack(k16, 0, eps=0.001)
+    assert e.value.status == bl.BLINK_EINVAL and time.time() - t0 < 1
+    assert abs(pack(k16, 0, eps=0.2).rate - 15.0) < 1e-9
+
+
 def test_trees_from_arrays_round_trip_and_rejects_non_trees():
     roots, parents, w = op.pack_trees(og.Digraph.from_topology(si.hybrid_cube_mesh()), 0)
     t = bl.blink_trees_from_arrays(8, roots, parents, w)
