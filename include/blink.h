@@ -57,7 +57,8 @@ typedef enum {
     BLINK_ENOMEM = 3,        /* host or device allocation failed */
     BLINK_EMISMATCH = 4,     /* schedule does not fit the call (k, n, collective) */
     BLINK_EHIP = 5,          /* a HIP runtime call failed (no device, launch error) */
-    BLINK_ESTUCK = 6         /* a stage gave up waiting for another one (see blink_schedule_status) */
+    BLINK_ESTUCK = 6,        /* a stage gave up waiting for another one (see blink_schedule_status) */
+    BLINK_ELIMIT = 7         /* the schedule does not fit the fixed device block of blink_allreduce_noalloc */
 } blink_status_t;
 
 typedef enum { BLINK_INT32 = 0, BLINK_FP32 = 1 } blink_dtype_t;
@@ -282,6 +283,28 @@ blink_status_t blink_allgather(void* const* bufs, int k, size_t n_elems, blink_d
                                blink_schedule_t* s, void* stream);
 blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
                             blink_schedule_t* s, void* stream);
+
+/* blink_allreduce for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result bit for bit; the call itself never allocates or frees
+ * device or host memory.  The schedule's device-side tables and progress
+ * counters do not go into an allocation of the schedule's own but into a block
+ * of fixed size that is part of the library's device image (4 MiB, held by
+ * every GPU the library has run on until the process ends).  Limit: the
+ * schedule's block, 256 bytes + 312 bytes per stage (blink_schedule_num_stages)
+ * + 88 bytes per distinct stage shape + 4 KiB, must fit into it, which allows
+ * about 13,000 stages (the per-edge program of 8 ranks x 256 MiB in 1 MiB
+ * chunks has 3,584); BLINK_ELIMIT otherwise, and nothing is launched.
+ * All calls of this function on one GPU share the block, whichever schedule
+ * they use: calls that overlap in time on one GPU race.  Each call clears the
+ * counters it needs on `stream` before its kernel.  When the block last held
+ * another schedule's tables the call first waits for `stream` and copies its own
+ * in synchronously (so under graph capture, make one call on the schedule
+ * beforehand).  blink_schedule_status reports on
+ * the block the latest call of the schedule used.  blink_allreduce and the other
+ * entry points are unaffected and may be mixed with this one on one schedule. */
+blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                                       blink_schedule_t* s, void* stream);
 
 /* Launch shape override for tuning: waves per compute unit (0 = automatic) and
  * elements per tile, the unit of work a wave draws at a time (0 = automatic;

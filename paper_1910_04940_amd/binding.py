@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libblink.so")
 
 BLINK_MAX_RANKS = 16
 BLINK_ROOT_ANY = -1
-BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP, BLINK_ESTUCK = range(7)
+BLINK_OK, BLINK_EINVAL, BLINK_EDISCONNECTED, BLINK_ENOMEM, BLINK_EMISMATCH, BLINK_EHIP, BLINK_ESTUCK, BLINK_ELIMIT = range(8)
 BLINK_INT32, BLINK_FP32 = 0, 1
 BLINK_OP_BROADCAST, BLINK_OP_ALLREDUCE, BLINK_OP_REDUCE, BLINK_OP_ALLGATHER, BLINK_OP_GATHER = 0, 1, 2, 3, 4
 BLINK_SUM, BLINK_PROD, BLINK_MIN, BLINK_MAX = 0, 1, 2, 3
@@ -51,7 +51,7 @@ EXPORTS = [
     "blink_miad_create", "blink_miad_chunk", "blink_miad_steady", "blink_miad_report",
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
     "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
-    "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call",
+    "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call", "blink_allreduce_noalloc",
 ]
 
 
@@ -126,7 +126,7 @@ def lib() -> C.CDLL:
     L.blink_schedule_traffic_bytes.restype = C.c_uint64
     L.blink_schedule_free.argtypes = [vp]
     L.blink_schedule_free.restype = None
-    for name in ("blink_allreduce", "blink_broadcast", "blink_allgather", "blink_gather"):
+    for name in ("blink_allreduce", "blink_broadcast", "blink_allgather", "blink_gather", "blink_allreduce_noalloc"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, vp, vp]
     for name in ("blink_allreduce_op", "blink_reduce"):
         getattr(L, name).argtypes = [C.POINTER(vp), C.c_int, C.c_size_t, C.c_int, C.c_int, vp, vp]
@@ -339,6 +339,13 @@ def blink_allreduce(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule
     arr = _pointers(bufs)
     _check(lib().blink_allreduce(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
            "blink_allreduce")
+
+
+def blink_allreduce_noalloc(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:
+    """blink_allreduce on the library's static device block: the call allocates nothing."""
+    arr = _pointers(bufs)
+    _check(lib().blink_allreduce_noalloc(arr, len(bufs), n_elems, dtype, schedule._h, C.c_void_p(stream)),
+           "blink_allreduce_noalloc")
 
 
 def blink_broadcast(bufs: Sequence, n_elems: int, dtype: int, schedule: Schedule, stream: int = 0) -> None:

@@ -93,6 +93,7 @@ blink_status_t blink_make_schedule(const blink_trees_t* trees, blink_op_t op, si
     if (!trees) return BLINK_EINVAL;
     BLINK_GUARD_BEGIN
     std::unique_ptr<blink_schedule_t> h(new blink_schedule_t());
+    h->id = blink::next_schedule_id();
     const blink_status_t st = blink::make_schedule(trees->t, op, n_elems, chunk_elems, fusion, h->s);
     if (st != BLINK_OK) return st;
     *out = h.release();
@@ -118,6 +119,7 @@ blink_status_t blink_make_schedule_servers(int n_servers, const blink_trees_t* c
         at += ks;
     }
     std::unique_ptr<blink_schedule_t> h(new blink_schedule_t());
+    h->id = blink::next_schedule_id();
     const blink_status_t st = blink::make_schedule_servers(servers, n_elems, chunk_elems, fusion, h->s);
     if (st != BLINK_OK) return st;
     *out = h.release();
@@ -195,6 +197,13 @@ blink_status_t blink_allreduce(void* const* bufs, int k, size_t n_elems, blink_d
                                blink_schedule_t* s, void* stream) {
     BLINK_GUARD_BEGIN
     return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, BLINK_SUM, stream);
+    BLINK_GUARD_END
+}
+
+blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,
+                                       blink_schedule_t* s, void* stream) {
+    BLINK_GUARD_BEGIN
+    return blink::execute(s, bufs, k, n_elems, dtype, BLINK_OP_ALLREDUCE, BLINK_SUM, stream, true);
     BLINK_GUARD_END
 }
 
@@ -280,6 +289,7 @@ const char* blink_strerror(blink_status_t st) {
         case BLINK_EMISMATCH: return "schedule does not match the call";
         case BLINK_EHIP: return "HIP runtime error";
         case BLINK_ESTUCK: return "a stage gave up waiting for another one";
+        case BLINK_ELIMIT: return "the schedule does not fit the static device block";
     }
     return "unknown status";
 }

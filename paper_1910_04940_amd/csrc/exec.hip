@@ -3,9 +3,42 @@
 // size, kernel flavour), the launch and its bookkeeping.
 #include "kernel.hpp"
 
+#include <atomic>
+#include <mutex>
+
 namespace blink {
 
 constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
+
+// ---- a device block that needs no allocation ------------------------------------------
+// For callers that may not allocate (a stream under HIP graph capture, a tight
+// serving loop, a harness that forbids it): a block of fixed size in the
+// library's own device image.  Every GPU the library runs on holds its own copy
+// of the array, at its own address, until the process ends; host code reaches
+// it only through the address hipGetSymbolAddress returns with that GPU current
+// (the array's name in host code is a host-side stand-in, not a device address).
+// All calls of blink_allreduce_noalloc on one GPU share that GPU's block.
+constexpr size_t kStaticBlockBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticBlockBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticBlock {
+    char* ptr = nullptr;   // device address of `scratch` on this GPU
+    uint64_t owner = 0;    // id of the schedule whose tables the block holds (0 = none)
+};
+StaticBlock g_static[kMaxDevices];
+std::mutex g_static_mutex;
+std::atomic<uint64_t> g_next_id{1};
+
+// Zeroes `words` 64-bit words (a fill kernel rather than hipMemsetAsync, which
+// must not be recorded into a captured graph).
+__global__ __launch_bounds__(256) void blink_clear(unsigned long long* p, unsigned long long words) {
+    for (unsigned long long i = blockIdx.x * 256ull + threadIdx.x; i < words; i += gridDim.x * 256ull) p[i] = 0;
+}
+}  // namespace
+
+uint64_t next_schedule_id() { return g_next_id.fetch_add(1); }
 
 // ---- host side ------------------------------------------------------------------------
 namespace {
@@ -67,6 +100,39 @@ blink_status_t upload(blink_schedule* h) {
     h->device = dev;
     h->epoch = 0;
     for (uint64_t& b : h->ticket_base) b = 0;
+    return BLINK_OK;
+}
+
+// The current device's static block, holding the tables of `h`.  The address is
+// looked up once per device.  The tables are copied in when the block last
+// held another schedule's (synchronously, after waiting for `stream`, whose
+// earlier calls may still be reading the old ones).  Allocates nothing.
+blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipStream_t stream, char** out) {
+    int dev = -1;
+    BLINK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return BLINK_ELIMIT;
+    if (l.bytes > kStaticBlockBytes) {
+        std::fprintf(stderr, "blink: the schedule needs a device block of %zu bytes, the static one has %zu\n",
+                     l.bytes, kStaticBlockBytes);
+        return BLINK_ELIMIT;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticBlock& sb = g_static[dev];
+    if (!sb.ptr) {
+        char* ptr = nullptr;
+        BLINK_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) return BLINK_EHIP;
+        sb.ptr = ptr;
+    }
+    if (sb.owner != h->id) {
+        sb.owner = 0;
+        BLINK_HIP(hipStreamSynchronize(stream));
+        BLINK_HIP(hipMemcpy(sb.ptr + l.tmpl, h->s.tmpl.data(), h->s.tmpl.size() * sizeof(StageTmpl), hipMemcpyHostToDevice));
+        BLINK_HIP(hipMemcpy(sb.ptr + l.inst, h->s.inst.data(), h->s.inst.size() * sizeof(StageInst), hipMemcpyHostToDevice));
+        sb.owner = h->id;
+    }
+    h->last_static_device = dev;
+    *out = sb.ptr;
     return BLINK_OK;
 }
 
@@ -156,10 +222,19 @@ blink_status_t reset_progress(blink_schedule* h) {
 blink_status_t read_status(blink_schedule* h, blink_progress_t* out) {
     *out = blink_progress_t{};
     out->stage = out->awaited_stage = -1;
-    if (h->device < 0) return BLINK_OK;  // never ran: nothing can have gone wrong
+    const void* block = h->d_block;
+    if (h->last_static_device >= 0) {  // the latest call ran on a static block: report on that one
+        int dev = -1;
+        BLINK_HIP(hipGetDevice(&dev));
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (dev != h->last_static_device || g_static[dev].owner != h->id) return BLINK_OK;  // record gone
+        block = g_static[dev].ptr;
+    } else if (h->device < 0) {
+        return BLINK_OK;  // never ran: nothing can have gone wrong
+    }
     unsigned long long rec[kStatusWords] = {};
     BLINK_HIP(hipDeviceSynchronize());
-    BLINK_HIP(hipMemcpy(rec, h->d_block, sizeof rec, hipMemcpyDeviceToHost));
+    BLINK_HIP(hipMemcpy(rec, block, sizeof rec, hipMemcpyDeviceToHost));
     out->state = static_cast<int32_t>(rec[kStatusState]);
     if (rec[kStatusState] == 0) return BLINK_OK;
     out->stage = static_cast<int32_t>(rec[kStatusStage]);
@@ -178,7 +253,7 @@ void release_device_state(blink_schedule* h) {
 }
 
 blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, blink_dtype_t dtype,
-                       blink_op_t op, blink_redop_t redop, void* stream) {
+                       blink_op_t op, blink_redop_t redop, void* stream, bool static_block) {
     if (!h || !bufs) return BLINK_EINVAL;
     if (dtype != BLINK_FP32 && dtype != BLINK_INT32) return BLINK_EINVAL;
     if (redop != BLINK_SUM && redop != BLINK_PROD && redop != BLINK_MIN && redop != BLINK_MAX) return BLINK_EINVAL;
@@ -194,11 +269,17 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         }
     }
     if (s.inst.empty()) return BLINK_OK;
-    if (blink_status_t st = upload(h)) return st;
+    const BlockLayout l = layout_of(s);
+    char* block = nullptr;
+    if (static_block) {
+        if (blink_status_t st = claim_static_block(h, l, static_cast<hipStream_t>(stream), &block)) return st;
+    } else {
+        if (blink_status_t st = upload(h)) return st;
+        block = static_cast<char*>(h->d_block);
+        h->last_static_device = -1;
+    }
     if (blink_status_t st = make_plan(h, dtype)) return st;
     const LaunchPlan& pl = h->plan;
-    const BlockLayout l = layout_of(s);
-    char* const block = static_cast<char*>(h->d_block);
 
     KernelFn fn = pick_kernel(dtype, pl.flavour, pl.wide);
     int& occ = h->occupancy[dtype == BLINK_FP32];
@@ -232,7 +313,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     const unsigned n_queues =
         static_cast<unsigned>(std::min<unsigned long long>(s.has_deps ? kQueuesHandOver : 1, grid));
     p.n_queues = n_queues;
-    for (unsigned q = 0; q < n_queues; ++q) p.ticket_base[q] = h->ticket_base[q];
+    // A static block is shared by every schedule used on the GPU and keeps the
+    // last call's contents: each call on it starts from cleared counters, as
+    // call number 1.  The schedule's own block counts on from call to call.
+    for (unsigned q = 0; q < n_queues; ++q) p.ticket_base[q] = static_block ? 0 : h->ticket_base[q];
     p.n_items = n_items;
     // A dependency-free schedule with at most four tickets per wave is dealt out
     // statically, without the counter (see the kernel).  Larger ones draw every
@@ -242,7 +326,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     // a ticket's holder known to be running.
     const unsigned long long static_items = (!s.has_deps && n_items / grid <= 4) ? n_items : 0;
     p.static_items = static_items;
-    p.epoch = h->epoch + 1;
+    p.epoch = static_block ? 1 : h->epoch + 1;
     p.tiles_per_chunk = pl.tiles_per_chunk;
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
@@ -257,6 +341,19 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     // earlier HIP call of this thread left behind is not this launch's, and a
     // launch that failed must not consume a call number or move the ticket
     // bases (the next call would wait for tiles that nobody ever counted).
+    if (static_block) {
+        unsigned long long* words = reinterpret_cast<unsigned long long*>(block);
+        unsigned long long n_words = l.counters_end / sizeof(unsigned long long);
+        void* clear_args[] = {&words, &n_words};
+        const unsigned clear_grid = static_cast<unsigned>(std::min<unsigned long long>((n_words + 255) / 256, 1024));
+        const hipError_t cleared = hipLaunchKernel(reinterpret_cast<const void*>(blink_clear), dim3(clear_grid), dim3(256),
+                                                   clear_args, 0, static_cast<hipStream_t>(stream));
+        if (cleared != hipSuccess) {
+            std::fprintf(stderr, "blink: kernel launch failed: %s\n", hipGetErrorString(cleared));
+            (void)hipGetLastError();
+            return BLINK_EHIP;
+        }
+    }
     void* args[] = {&p};
     const hipError_t launched = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3(static_cast<unsigned>(grid)),
                                                 dim3(kLanes), args, 0, static_cast<hipStream_t>(stream));
@@ -265,6 +362,8 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         (void)hipGetLastError();  // the failed launch's error is reported here, not left for later calls
         return BLINK_EHIP;
     }
+    h->last_grid = static_cast<unsigned>(grid);
+    if (static_block) return BLINK_OK;
     h->epoch += 1;
     if (static_items < n_items) {
         // queue q holds the drawn tickets q, q + n_queues, ...; every wave

@@ -39,6 +39,7 @@ struct blink_schedule {
     blink::LaunchPlan plan;
     int device = -1;              // HIP device holding the block; -1 = not uploaded yet
     void* d_block = nullptr;      // see BlockLayout
+    uint64_t id = 0;              // unique per handle (names the owner of a device's static block)
     uint64_t epoch = 0;           // calls made so far on d_block; its counters hold epoch * tiles
     uint64_t ticket_base[16] = {};  // value of each ticket counter when the next call starts
     uint64_t wait_limit_us = 0;   // longest wait for another stage; 0 = default
@@ -47,11 +48,14 @@ struct blink_schedule {
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
     int occupancy[2] = {0, 0};    // waves per CU of the plan's kernel, per dtype
     unsigned last_grid = 0;
+    int last_static_device = -1;  // device whose static block the latest call used; -1 = it used d_block
 };
 
 namespace blink {
+// static_block: run on the device's file-scope block instead of the schedule's own.
 blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, blink_dtype_t dtype,
-                       blink_op_t op, blink_redop_t redop, void* stream);
+                       blink_op_t op, blink_redop_t redop, void* stream, bool static_block = false);
+uint64_t next_schedule_id();
 blink_status_t reset_progress(blink_schedule* h);
 blink_status_t read_status(blink_schedule* h, blink_progress_t* out);
 void release_device_state(blink_schedule* h);
