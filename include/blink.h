@@ -126,7 +126,13 @@ typedef struct {
  * (i < n_load); then the n_op micro-operations in order, each (kind << 6) | slot
  * with kind 0: acc <- slot, 1: acc <- acc (+) slot, 2: slot <- acc; finally acc
  * is stored to every rank in store_rank[0 .. n_store).  deps: indices of the
- * earlier stages all of which must have finished on their whole chunk first. */
+ * earlier stages all of which must have finished on their whole chunk first.
+ * seq_*: the same computation as a program for a stack of accumulators (what the
+ * streaming kernel runs): for i < n_load in turn, rank seq_rank[i] either starts
+ * a new accumulator on top of the stack (seq_code[i] & 1) or is combined into
+ * the top one; then seq_code[i] >> 1 times the top accumulator is combined into
+ * the one below it and dropped.  One accumulator is left: the result.
+ * seq_depth: the accumulators needed; 0 when the stage has no such form. */
 #define BLINK_STAGE_MAX_OPS 40
 #define BLINK_STAGE_MAX_DEPS 8
 typedef struct {
@@ -141,6 +147,10 @@ typedef struct {
     uint8_t store_rank[BLINK_MAX_RANKS];
     uint8_t op[BLINK_STAGE_MAX_OPS];
     int32_t deps[BLINK_STAGE_MAX_DEPS];
+    uint8_t seq_rank[BLINK_MAX_RANKS];
+    uint8_t seq_code[BLINK_MAX_RANKS];
+    uint8_t seq_depth;
+    uint8_t reserved[3];
 } blink_stage_t;
 
 /* ---- tree packing (host only; no GPU needed) ------------------------------ */
@@ -312,6 +322,18 @@ blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems,
  * device and restarts the schedule's progress counters.  Applies to later
  * calls on this schedule. */
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
+/* Two kernels can run a sum over a schedule whose stages do not wait for one
+ * another (whole-tree fusion) at streaming sizes; they give the same bits.
+ * kernel: 0 = automatic (the first four calls of at least 64 MiB of traffic
+ * alternate between the two and are timed with events on the caller's stream;
+ * the fifth call waits for them and the faster kernel serves from then on;
+ * blink_allreduce_noalloc takes no part in the timing), 1 = the ticket-drawing kernel with
+ * loads staged through registers, 2 = the streaming kernel with loads straight
+ * into LDS.  Schedules only one of them can run are not affected.
+ * blink_schedule_last_kernel: the kernel the latest call ran on (1 or 2; 0
+ * before the first call). */
+blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel);
+int blink_schedule_last_kernel(const blink_schedule_t* s);
 
 /* What became of the calls made on a schedule so far.  In the per-edge and
  * per-node programs a stage waits, chunk by chunk, for the stages it depends on

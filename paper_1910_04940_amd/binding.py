@@ -39,7 +39,8 @@ PROGRESS_DTYPE = np.dtype([("state", "<i4"), ("stage", "<i4"), ("awaited_stage",
 STAGE_DTYPE = np.dtype([("off", "<u8"), ("len", "<u4"), ("tree", "<i4"), ("chunk", "<i4"), ("flow", "<i4"),
                         ("n_load", "u1"), ("n_op", "u1"), ("n_store", "u1"), ("n_dep", "u1"),
                         ("load_rank", "u1", (16,)), ("store_rank", "u1", (16,)), ("op", "u1", (40,)),
-                        ("deps", "<i4", (8,))], align=True)
+                        ("deps", "<i4", (8,)), ("seq_rank", "u1", (16,)), ("seq_code", "u1", (16,)),
+                        ("seq_depth", "u1"), ("reserved", "u1", (3,))], align=True)
 
 EXPORTS = [
     "blink_pack_trees", "blink_trees_from_arrays", "blink_trees_count", "blink_trees_k",
@@ -52,6 +53,7 @@ EXPORTS = [
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
     "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
     "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call", "blink_allreduce_noalloc",
+    "blink_schedule_set_kernel", "blink_schedule_last_kernel",
 ]
 
 
@@ -135,6 +137,8 @@ def lib() -> C.CDLL:
     L.blink_schedule_reset.argtypes = [vp]
     L.blink_schedule_set_wait_limit.argtypes = [vp, C.c_uint64]
     L.blink_schedule_test_skip_call.argtypes = [vp]
+    L.blink_schedule_set_kernel.argtypes = [vp, C.c_int]
+    L.blink_schedule_last_kernel.argtypes = [vp]
     L.blink_miad_create.argtypes = [C.c_size_t, C.c_double, C.c_size_t, C.c_size_t, C.c_size_t,
                                     C.c_double, C.POINTER(vp)]
     L.blink_miad_chunk.argtypes = [vp]
@@ -276,6 +280,13 @@ class Schedule:
 
     def set_launch(self, wg_per_cu: int = 0, tile_elems: int = 0) -> None:
         _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, tile_elems), "blink_schedule_set_launch")
+
+    def set_kernel(self, kernel: int) -> None:
+        _check(lib().blink_schedule_set_kernel(self._h, kernel), "blink_schedule_set_kernel")
+
+    @property
+    def last_kernel(self) -> int:
+        return lib().blink_schedule_last_kernel(self._h)
 
     def status(self) -> Tuple[int, dict]:
         """(status code, blink_progress_t as a dict); waits for the device."""

@@ -20,6 +20,11 @@ FLAGS = [
     "-fno-gpu-flush-denormals-to-zero",      # fp32 subnormals are ordinary addends
     "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # A ticket is drawn by lane 0 alone.  The compiler's wave-level rewriting of
+    # atomics (one lane adds for all, the others derive their values) gains
+    # nothing there and reads the counter's answer, hence waits for it, right
+    # after the atomic; without it the answer travels while loads are issued.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -174,6 +174,9 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
         std::memcpy(o.load_rank, st.load_rank, sizeof o.load_rank);
         std::memcpy(o.store_rank, st.store_rank, sizeof o.store_rank);
         std::memcpy(o.op, st.op, sizeof o.op);
+        std::memcpy(o.seq_rank, st.seq_rank, sizeof o.seq_rank);
+        std::memcpy(o.seq_code, st.seq_code, sizeof o.seq_code);
+        o.seq_depth = st.seq_depth;
         for (int d = 0; d < BLINK_STAGE_MAX_DEPS; ++d) o.deps[d] = d < static_cast<int>(in.n_dep) ? in.dep[d] : -1;
     }
     return BLINK_OK;
@@ -279,6 +282,14 @@ blink_status_t blink_schedule_test_skip_call(blink_schedule_t* s) {
     s->epoch += 1;
     return BLINK_OK;
 }
+
+blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel) {
+    if (!s || kernel < 0 || kernel > 2) return BLINK_EINVAL;
+    s->kernel_choice = kernel;
+    return BLINK_OK;
+}
+
+int blink_schedule_last_kernel(const blink_schedule_t* s) { return s ? s->last_kernel : 0; }
 
 const char* blink_strerror(blink_status_t st) {
     switch (st) {

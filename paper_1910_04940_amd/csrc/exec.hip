@@ -1,7 +1,7 @@
 // The launcher of the persistent kernel (see kernel.hpp): the device block of a
 // schedule (status record, progress counters, tables), the launch plan (tile
 // size, kernel flavour), the launch and its bookkeeping.
-#include "kernel.hpp"
+#include "stream.hpp"
 
 #include <atomic>
 #include <mutex>
@@ -43,6 +43,8 @@ uint64_t next_schedule_id() { return g_next_id.fetch_add(1); }
 // ---- host side ------------------------------------------------------------------------
 namespace {
 
+void drop_trial_events(blink_schedule* h);  // below, with the choice between the two kernels
+
 #define BLINK_HIP(call)                                                                   \
     do {                                                                                  \
         hipError_t err__ = (call);                                                        \
@@ -52,9 +54,9 @@ namespace {
         }                                                                                 \
     } while (0)
 
-KernelFn pick_kernel(blink_dtype_t dtype, int flavour, bool many_waves) {
-    if (dtype == BLINK_FP32) return many_waves ? kernel_f32_many(flavour) : kernel_f32_stream(flavour);
-    return many_waves ? kernel_i32_many(flavour) : kernel_i32_stream(flavour);
+KernelFn pick_kernel(blink_dtype_t dtype, int flavour, bool many_waves, bool direct) {
+    if (dtype == BLINK_FP32) return many_waves ? kernel_f32_many(flavour) : kernel_f32_stream(flavour, direct);
+    return many_waves ? kernel_i32_many(flavour) : kernel_i32_stream(flavour, direct);
 }
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -176,9 +178,9 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
                  : (pl.read_heavy || fits_cache) ? kReadHeavy
                                                  : kBalanced;
     if (pl.wide) {
-        int& occ = h->occupancy[dtype == BLINK_FP32];
+        int& occ = h->occupancy[dtype == BLINK_FP32][0];
         if (occ == 0) {
-            BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, pick_kernel(dtype, pl.flavour, true), kLanes, 0));
+            BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, pick_kernel(dtype, pl.flavour, true, false), kLanes, 0));
             if (occ < 1) {
                 occ = 0;
                 return BLINK_EHIP;
@@ -186,6 +188,11 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
         }
         while (tile > kMinTile && work / tile < static_cast<uint64_t>(occ) * h->n_cu / 2) tile /= 2;
     }
+    // The streaming kernel (stream.hpp) takes schedules without dependencies all
+    // of whose stages have a stack program within its limits.
+    pl.direct = !pl.wide && !s.has_deps;
+    for (const StageTmpl& st : s.tmpl)
+        if (st.seq_depth < 1 || st.seq_depth > stream_stack_limit(st.n_load)) pl.direct = false;
     if (h->tile_override) tile = h->tile_override;
     pl.tile_elems = tile;
     pl.tile_shift = 0;
@@ -210,7 +217,10 @@ blink_status_t reset_progress(blink_schedule* h) {
     h->epoch = 0;
     for (uint64_t& b : h->ticket_base) b = 0;
     h->plan = LaunchPlan();
-    h->occupancy[0] = h->occupancy[1] = 0;
+    for (auto& per_dtype : h->occupancy) per_dtype[0] = per_dtype[1] = 0;
+    drop_trial_events(h);
+    h->picked = 0;
+    h->trial_calls = 0;
     if (h->device < 0) return BLINK_OK;
     BLINK_HIP(hipDeviceSynchronize());
     BLINK_HIP(hipMemset(h->d_block, 0, layout_of(h->s).counters_end));
@@ -245,7 +255,70 @@ blink_status_t read_status(blink_schedule* h, blink_progress_t* out) {
     return BLINK_ESTUCK;
 }
 
+// Picking between the two kernels.  A schedule that both can run (no
+// dependencies, streaming size, sum) is served fastest by blink_consume on most
+// placements of the caller's buffers, but on some blink_consume loses a quarter
+// of its throughput and blink_stream, which is steadier, wins; which is which
+// depends on where the buffers lie in HBM, in ways addresses do not reveal.  So
+// the first kTrialCalls calls on such a schedule alternate between the two,
+// each timed with a pair of events on the caller's stream; the next call waits
+// for the last of them (the one time a call waits for the device, besides a
+// schedule's first) and the kernel with the smaller minimum serves the rest.
+// Both give the same bits.
+constexpr int kTrialCalls = 4;
+constexpr uint64_t kTrialMinBytes = 64ull << 20;  // smaller calls are too short to time against one another
+
+namespace {
+void drop_trial_events(blink_schedule* h) {
+    for (void*& e : h->trial_event) {
+        if (e) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
+        e = nullptr;
+    }
+    h->trial_events_made = false;
+}
+
+// 1 = blink_consume, 2 = blink_stream for this call; *timed: index of the event pair to put around it, or -1.
+int choose_kernel(blink_schedule* h, bool static_block, int* timed) {
+    *timed = -1;
+    if (h->kernel_choice) return h->kernel_choice;
+    if (h->picked) return h->picked;
+    if (static_block || h->s.traffic_bytes < kTrialMinBytes) return 1;  // no trial: nothing may be created here / too short
+    if (h->trial_calls < kTrialCalls) {
+        if (!h->trial_events_made) {
+            for (void*& e : h->trial_event) {
+                hipEvent_t ev = nullptr;
+                if (hipEventCreate(&ev) != hipSuccess) {
+                    (void)hipGetLastError();
+                    drop_trial_events(h);
+                    h->picked = 1;
+                    return 1;
+                }
+                e = ev;
+            }
+            h->trial_events_made = true;
+        }
+        *timed = h->trial_calls;
+        return 1 + (h->trial_calls & 1);
+    }
+    // All trial calls are launched: wait for the last of them (once per
+    // schedule, at its fifth call) and compare.
+    float best[2] = {1e30f, 1e30f};
+    bool ok = hipEventSynchronize(static_cast<hipEvent_t>(h->trial_event[2 * kTrialCalls - 1])) == hipSuccess;
+    for (int c = 0; ok && c < kTrialCalls; ++c) {
+        float ms = 0.f;
+        ok = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(h->trial_event[2 * c]),
+                                 static_cast<hipEvent_t>(h->trial_event[2 * c + 1])) == hipSuccess;
+        best[c & 1] = std::min(best[c & 1], ms);
+    }
+    if (!ok) (void)hipGetLastError();
+    h->picked = ok && best[1] < best[0] ? 2 : 1;
+    drop_trial_events(h);
+    return h->picked;
+}
+}  // namespace
+
 void release_device_state(blink_schedule* h) {
+    drop_trial_events(h);
     if (h->device < 0) return;
     (void)hipFree(h->d_block);
     h->d_block = nullptr;
@@ -281,8 +354,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     if (blink_status_t st = make_plan(h, dtype)) return st;
     const LaunchPlan& pl = h->plan;
 
-    KernelFn fn = pick_kernel(dtype, pl.flavour, pl.wide);
-    int& occ = h->occupancy[dtype == BLINK_FP32];
+    int timed = -1;
+    const bool direct = pl.direct && redop == BLINK_SUM && choose_kernel(h, static_block, &timed) == 2;
+    KernelFn fn = pick_kernel(dtype, pl.flavour, pl.wide, direct);
+    int& occ = h->occupancy[dtype == BLINK_FP32][direct];
     if (occ == 0) {
         BLINK_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, kLanes, 0));
         if (occ < 1) {
@@ -290,12 +365,11 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
             return BLINK_EHIP;
         }
     }
-    // A few waves per CU, each with 32 KiB of loads in flight, saturate HBM;
-    // more waves only add ticket and polling traffic.  Measured best: 2, and 3
-    // where reads dominate (Reduce: 8 ranks read, 1 written, 0.485 -> 0.412 ms),
-    // where stages wait for one another, or where a stage reads more than 8
-    // ranks (only 2 columns per rank fit then; 12 ranks: 5.14 -> 5.43 TB/s).
-    int per_cu = std::min(occ, pl.read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2);
+    // Waves per CU.  blink_stream: 2, each with 64 KiB of loads in flight (all
+    // that fit).  blink_consume: 2 waves with 32 KiB each, 3 where stages wait for
+    // one another, where reads dominate, or where a stage reads more than 8 ranks
+    // (only 2 columns per rank fit then).
+    int per_cu = std::min(occ, direct ? 2 : (pl.read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2));
     if (h->wg_per_cu > 0) per_cu = std::min(occ, h->wg_per_cu);
     if (pl.wide && h->wg_per_cu == 0) per_cu = occ;
     const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
@@ -330,8 +404,12 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tiles_per_chunk = pl.tiles_per_chunk;
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
-    // Without dependencies the order of tiles is free: interleave the trees tile by tile.
-    p.group = s.has_deps ? 1u : std::min(64u, std::max(1u, s.n_flows));
+    // Without dependencies the order of tiles is free: the trees are interleaved
+    // tile by tile (section 4.2.2), all of them while a stage reads at most 8
+    // ranks.  With more ranks per stage that makes too many request streams at a
+    // time (16 ranks x 16 one-hop trees = 256): there the trees take turns chunk
+    // by chunk (16 x 1 GiB: 5.5 -> 5.9 TB/s; two servers of 8: 5.7 -> 5.9).
+    p.group = s.has_deps || s.max_slots > 8 ? 1u : std::min(64u, std::max(1u, s.n_flows));
     // Waiting waves look at their dependency every ~0.2 us in small schedules,
     // where a hand-over is most of the time (16 one-hop trees, 256 elements,
     // per-edge: 47 -> 36 us), and back off to ~0.8 us in large ones.
@@ -355,6 +433,13 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         }
     }
     void* args[] = {&p};
+    if (timed >= 0 && hipEventRecord(static_cast<hipEvent_t>(h->trial_event[2 * timed]),
+                                     static_cast<hipStream_t>(stream)) != hipSuccess) {
+        (void)hipGetLastError();  // e.g. a capturing stream: give the trial up
+        drop_trial_events(h);
+        h->picked = 1;
+        timed = -1;
+    }
     const hipError_t launched = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3(static_cast<unsigned>(grid)),
                                                 dim3(kLanes), args, 0, static_cast<hipStream_t>(stream));
     if (launched != hipSuccess) {
@@ -362,7 +447,18 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         (void)hipGetLastError();  // the failed launch's error is reported here, not left for later calls
         return BLINK_EHIP;
     }
+    if (timed >= 0) {
+        if (hipEventRecord(static_cast<hipEvent_t>(h->trial_event[2 * timed + 1]), static_cast<hipStream_t>(stream)) ==
+            hipSuccess) {
+            h->trial_calls += 1;
+        } else {
+            (void)hipGetLastError();
+            drop_trial_events(h);
+            h->picked = 1;
+        }
+    }
     h->last_grid = static_cast<unsigned>(grid);
+    h->last_kernel = direct ? 2 : 1;
     if (static_block) return BLINK_OK;
     h->epoch += 1;
     if (static_items < n_items) {

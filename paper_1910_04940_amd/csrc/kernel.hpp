@@ -535,8 +535,8 @@ KernelFn pick_kernel_of(int flavour) {
 // Each is defined in a translation unit of its own, so that the four compile
 // side by side.
 KernelFn kernel_f32_many(int flavour);
-KernelFn kernel_f32_stream(int flavour);
+KernelFn kernel_f32_stream(int flavour, bool direct);
 KernelFn kernel_i32_many(int flavour);
-KernelFn kernel_i32_stream(int flavour);
+KernelFn kernel_i32_stream(int flavour, bool direct);
 
 }  // namespace blink

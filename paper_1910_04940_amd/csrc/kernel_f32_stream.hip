@@ -1,8 +1,8 @@
-// Instantiations of the kernel: fp32 elements, 32 columns per lane.  See kernel.hpp.
-#include "kernel.hpp"
+// Instantiations of the kernels for payloads that stream: fp32 elements.  See stream.hpp.
+#include "stream.hpp"
 
 namespace blink {
 
-KernelFn kernel_f32_stream(int flavour) { return pick_kernel_of<float, kColumnsStream>(flavour); }
+KernelFn kernel_f32_stream(int flavour, bool direct) { return pick_stream_kernel_of<float>(flavour, direct); }
 
 }  // namespace blink

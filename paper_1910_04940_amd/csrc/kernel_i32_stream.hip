@@ -1,8 +1,8 @@
-// Instantiations of the kernel: int32 elements (added as unsigned: wrap-around), 32 columns per lane.  See kernel.hpp.
-#include "kernel.hpp"
+// Instantiations of the kernels for payloads that stream: wrap-around int32 elements.  See stream.hpp.
+#include "stream.hpp"
 
 namespace blink {
 
-KernelFn kernel_i32_stream(int flavour) { return pick_kernel_of<unsigned, kColumnsStream>(flavour); }
+KernelFn kernel_i32_stream(int flavour, bool direct) { return pick_stream_kernel_of<unsigned>(flavour, direct); }
 
 }  // namespace blink

@@ -231,6 +231,51 @@ std::vector<StageTmpl> tree_stage(int k, int root, const ParentVec& parent, uint
     return {t};
 }
 
+}  // namespace
+
+void stack_program(StageTmpl& st) {
+    st.seq_depth = 0;
+    for (int i = 0; i < BLINK_MAX_RANKS; ++i) st.seq_rank[i] = st.seq_code[i] = 0;
+    enum : int { kLoaded = -1, kUsed = -2 };   // else: depth at which a partial sum is parked in the slot
+    int state[64];
+    for (int i = 0; i < 64; ++i) state[i] = i < st.n_load ? kLoaded : kUsed;
+    int depth = 0, deepest = 0, n = 0;
+    uint8_t rank[BLINK_MAX_RANKS], code[BLINK_MAX_RANKS];
+    for (int o = 0; o < st.n_op; ++o) {
+        const int kind = st.op[o] >> 6, slot = st.op[o] & 63;
+        if (kind == OP_ST) {
+            if (depth < 1 || state[slot] != kUsed) return;  // parks only into a slot whose value is spent
+            state[slot] = depth;
+        } else if (state[slot] == kLoaded) {
+            if (n == BLINK_MAX_RANKS) return;
+            if (kind == OP_LD) {
+                ++depth;
+                deepest = std::max(deepest, depth);
+            } else if (depth < 1) {
+                return;
+            }
+            rank[n] = st.load_rank[slot];
+            code[n] = kind == OP_LD ? 1 : 0;
+            ++n;
+            state[slot] = kUsed;
+        } else {
+            // a parked partial sum: must be the accumulator right below the top
+            if (kind != OP_ADD || state[slot] != depth - 1 || n == 0 || (code[n - 1] >> 1) == 63) return;
+            code[n - 1] = static_cast<uint8_t>(code[n - 1] + 2);
+            --depth;
+            state[slot] = kUsed;
+        }
+    }
+    if (depth != 1 || n != st.n_load) return;
+    for (int i = 0; i < n; ++i) {
+        st.seq_rank[i] = rank[i];
+        st.seq_code[i] = code[i];
+    }
+    st.seq_depth = static_cast<uint8_t>(deepest);
+}
+
+namespace {
+
 void finish_levels(std::vector<StageTmpl>& st) {
     for (size_t j = 0; j < st.size(); ++j) {
         int lvl = 0;
@@ -408,9 +453,12 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
     out.traffic_bytes = 0;
     out.read_bytes = 0;
     out.has_deps = false;
-    for (const StageTmpl& st : out.tmpl) {
+    out.max_stack = 0;
+    for (StageTmpl& st : out.tmpl) {
+        stack_program(st);
         out.max_slots = std::max<uint32_t>(out.max_slots, st.n_load);
         out.has_deps = out.has_deps || st.n_dep > 0;
+        out.max_stack = std::max<uint32_t>(out.max_stack, st.seq_depth ? st.seq_depth : 255u);
     }
     for (const StageInst& in : out.inst) {
         const StageTmpl& st = out.tmpl[in.tmpl];

@@ -28,6 +28,14 @@ struct alignas(4) StageTmpl {
     uint8_t store_rank[BLINK_MAX_RANKS];
     uint8_t op[kMaxOps];
     uint8_t dep_local[kMaxDeps];     // host only: index of the awaited stage among the tree's stages
+    // The same micro-program as a stack program over the loaded ranks in the
+    // order in which `op` consumes them (see stack_program): seq_rank[i] is the
+    // i-th rank consumed, seq_code[i] = (folds << 1) | push.  seq_depth: the
+    // accumulators it needs; 0 = `op` has no such form.
+    uint8_t seq_rank[BLINK_MAX_RANKS];
+    uint8_t seq_code[BLINK_MAX_RANKS];
+    uint8_t seq_depth;
+    uint8_t pad2[3];
 };
 
 // One stage applied to one chunk.  Plain data: copied to the device as is.
@@ -40,6 +48,18 @@ struct StageInst {
     int32_t dep[kMaxDeps];           // indices of earlier instances
 };
 static_assert(sizeof(StageTmpl) % 4 == 0, "StageTmpl is read as 32-bit words");
+
+// Rewrite st.op as a program for a stack of accumulators, which a kernel can
+// run on registers alone: the ranks in the order in which they are consumed,
+// each either starting a new accumulator on top of the stack (push) or being
+// combined into the top one, followed by `folds` times "combine the top
+// accumulator into the one below and drop it".  In `op` terms: LD pushes, ADD
+// of a loaded slot combines, ST parks the top accumulator (it simply stays where
+// it is while a later LD pushes above it) and ADD of a parked slot folds.  The
+// association order is that of `op`; as there, only commutativity of the
+// operator is used.  Fills seq_rank, seq_code, seq_depth (0 if `op` does not have
+// this shape: a slot consumed twice or never, a fold that is not innermost).
+void stack_program(StageTmpl& st);
 
 // Where a stage instance belongs: the packed tree, the chunk inside the flow's
 // range, and the flow (one tree carrying one contiguous range in one direction;
@@ -61,6 +81,7 @@ struct Schedule {
     std::vector<StageInst> inst;         // execution (ticket) order; dependencies point backwards
     std::vector<InstWhere> inst_where;   // per instance: what it belongs to
     uint32_t max_slots = 1;              // largest n_load
+    uint32_t max_stack = 0;              // most accumulators any stage's stack program needs (255: some stage has none)
     bool has_deps = false;               // some stage waits for another
     uint64_t traffic_bytes = 0;          // bytes read plus written in rank buffers per call
     uint64_t read_bytes = 0;             // the part of it that is read

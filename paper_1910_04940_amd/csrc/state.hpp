@@ -21,6 +21,7 @@ struct LaunchPlan {
     uint32_t tiles_per_chunk = 1;  // most tiles any stage instance has
     uint64_t n_items = 0;          // tickets per call
     bool read_heavy = false;
+    bool direct = false;           // the schedule CAN run on the streaming kernel (stream.hpp)
 };
 
 // Layout of the device block of a schedule, in bytes from its start:
@@ -46,9 +47,16 @@ struct blink_schedule {
     int n_cu = 0;
     int wg_per_cu = 0;            // launch override (0 = automatic)
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
-    int occupancy[2] = {0, 0};    // waves per CU of the plan's kernel, per dtype
+    int occupancy[2][2] = {};     // waves per CU of the kernel in use, per dtype and per (streaming kernel or not)
     unsigned last_grid = 0;
+    int last_kernel = 0;          // the kernel the latest call ran on: 1 = blink_consume, 2 = blink_stream
     int last_static_device = -1;  // device whose static block the latest call used; -1 = it used d_block
+    // Which of the two kernels serves a schedule that both can run (see execute):
+    int kernel_choice = 0;        // the caller's wish: 0 = pick the faster, 1 = blink_consume, 2 = blink_stream
+    int picked = 0;               // the pick once made (1 or 2); 0 = not yet
+    int trial_calls = 0;          // timed calls launched so far (they alternate between the two kernels)
+    void* trial_event[8] = {};    // hipEvent_t pairs around the timed calls
+    bool trial_events_made = false;
 };
 
 namespace blink {

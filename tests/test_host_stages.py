@@ -62,6 +62,25 @@ def run_stages(bufs, stages, order, redop=ox.SUM):
             else:
                 assert kind == ST
                 slots[slot] = acc.copy()
+        # the same stage as a stack program (what the streaming kernel runs):
+        # every stage has one, and it gives the same bits
+        assert 1 <= int(s["seq_depth"]) <= max(1, int(s["n_load"]) // 2), "stage without a stack program"
+        stack, deepest = [], 0
+        for j in range(int(s["n_load"])):
+            x = bufs[int(s["seq_rank"][j])][a:b]
+            code = int(s["seq_code"][j])
+            if code & 1:
+                stack.append(x.copy())
+            else:
+                stack[-1] = ox.combine(stack[-1], x, redop)
+            deepest = max(deepest, len(stack))
+            for _ in range(code >> 1):
+                top = stack.pop()
+                stack[-1] = ox.combine(stack[-1], top, redop)
+        assert len(stack) == 1 and deepest == int(s["seq_depth"])
+        assert sorted(int(r) for r in s["seq_rank"][:int(s["n_load"])]) == \
+            sorted(int(r) for r in s["load_rank"][:int(s["n_load"])])
+        assert np.array_equal(stack[0].view(np.uint32), acc.view(np.uint32))
         for r in s["store_rank"][:int(s["n_store"])]:
             bufs[int(r)][a:b] = acc
 
@@ -205,3 +224,41 @@ def test_the_race_check_catches_a_dropped_dependency():
     stages[victim]["n_dep"] = 0
     with pytest.raises(AssertionError):
         check_no_unordered_conflicts(stages)
+
+
+def test_stack_programs_of_deep_and_random_trees():
+    """Depth of the stack program: a caterpillar whose every second child is the
+    next internal node needs one accumulator per level (k / 2 of them), which is
+    the worst case; random trees stay within n_load / 2 and replay correctly."""
+    k = 16
+    parent = [-1] + [0] * (k - 1)
+    # vertex 0: children 1 (leaf) and 2; vertex 2: children 3 (leaf) and 4; ...
+    for v in range(1, k):
+        parent[v] = v - 1 if v % 2 == 1 else v - 2
+    trees = bl.blink_trees_from_arrays(k, [0], [parent], [1.0])
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 4096, 1024, bl.BLINK_FUSE_TREE)
+    stages = sched.stages()
+    assert int(stages[0]["seq_depth"]) == k // 2
+    x = [si.payload(8, r, 4096, "uniform", "fp32") for r in range(k)]
+    want = ox.tree_order_allreduce(x, [0], [tuple(parent)], [1.0])
+    bufs = [a.copy() for a in x]
+    run_stages(bufs, stages, list(range(len(stages))))
+    assert all(np.array_equal(b.view(np.uint32), want.view(np.uint32)) for b in bufs)
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        k = int(rng.integers(2, 17))
+        order = rng.permutation(k)
+        parent = [0] * k
+        parent[order[0]] = -1
+        for i in range(1, k):
+            parent[order[i]] = int(order[rng.integers(0, i)])
+        root = int(order[0])
+        trees = bl.blink_trees_from_arrays(k, [root], [parent], [1.0])
+        for fusion in FUSIONS:
+            sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 1000, 256, fusion)
+            stages = sched.stages()
+            x = [si.payload(9, r, 1000, "uniform", "fp32") for r in range(k)]
+            want = ox.tree_order_allreduce(x, [root], [tuple(parent)], [1.0])
+            bufs = [a.copy() for a in x]
+            run_stages(bufs, stages, topological_order(stages, 3))
+            assert all(np.array_equal(b.view(np.uint32), want.view(np.uint32)) for b in bufs)
