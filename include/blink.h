@@ -248,6 +248,19 @@ blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t*
 /* out[num_stages] (host, caller-allocated): the kernel's passes in the order
  * in which their tickets are handed out (a topological order of the deps). */
 blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_t* out);
+/* The order in which the kernel hands out its work when a tile has tile_elems
+ * elements (a power of two in [256, 65536]; the library's own choice depends on
+ * the device): ticket t is tile tile[t] of stage stage[t] (an index into
+ * blink_schedule_get_stages; tile i of a stage covers the stage's elements in
+ * block (off / tile_elems + i) of the payload's tile_elems-element blocks), or
+ * tile[t] == -1 for a ticket that stands for nothing (stages shorter than the
+ * longest one).  Wavefronts take tickets in ascending order.  Where the order
+ * is free (no stage waits for another) the tickets walk tile by tile across the
+ * trees (section 4.2.2: trees sharing the machine take turns) unless a stage
+ * reads more than 8 ranks.  *n_tickets receives the count; stage and tile (host,
+ * caller-allocated, that many entries) may both be null to ask for the count. */
+blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t tile_elems, uint64_t* n_tickets,
+                                          int32_t* stage, int32_t* tile);
 /* out[T+1] (host): share boundaries b_0 = 0 .. b_T = n_elems. */
 blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out);
 /* Bytes the kernel reads plus writes in rank buffers for one call with 4-byte

@@ -161,8 +161,9 @@ def emit_tree_steps(steps: List[Step], t: int, root: int, parent: Sequence[int],
 
 
 # --------------------------------------------------------------------------
-# Gather and AllGather (section 4.1: "Gather is the inverse of Broadcast, and
-# AllGather is AllReduce without using a reduction function")
+# Gather and AllGather (section 4.1 derives them from the collectives above: a
+# gather runs a broadcast backwards, an all-gather is an all-reduce that only
+# moves data)
 # --------------------------------------------------------------------------
 # Every rank buffer has n = k * m elements; rank j owns piece j = [j*m, (j+1)*m)
 # and starts with it in place.  Each piece is split among the trees by weight
@@ -387,15 +388,55 @@ def _symbolic_replay(steps, idx, k, root, parent, op, ch=None) -> None:
         assert val[v][0] == want, f"rank {v} ends with {val[v][0]}, expected {want}"
 
 
-def pipeline_makespan(steps: Sequence[Step]) -> int:
-    """Length, in unit chunk-transfer times, of the schedule when every step
-    takes one time unit, starts once its dependencies are done, and a directed
-    link (src, dst) carries one step at a time in list order.  Used for the
-    chunking claim of section 4.2.1 (h hops, c equal chunks: h + c - 1)."""
-    finish: List[int] = []
+def link_timeline(steps: Sequence[Step]) -> List[int]:
+    """Start time of every step when each takes one time unit, starts once its
+    dependencies are done, and a directed link (src, dst) carries one step at a
+    time, serving the steps that use it in list order (what a stream per link
+    does, sections 4.1 and 4.2.2)."""
+    start: List[int] = []
     link_free: Dict[Tuple[int, int], int] = {}
     for s in steps:
-        start = max([finish[d] for d in s.deps] + [link_free.get((s.src, s.dst), 0)])
-        finish.append(start + 1)
-        link_free[(s.src, s.dst)] = start + 1
-    return max(finish) if finish else 0
+        at = max([start[d] + 1 for d in s.deps] + [link_free.get((s.src, s.dst), 0)])
+        start.append(at)
+        link_free[(s.src, s.dst)] = at + 1
+    return start
+
+
+def pipeline_makespan(steps: Sequence[Step]) -> int:
+    """Length, in unit chunk-transfer times, of the schedule under link_timeline.
+    Used for the chunking claim of section 4.2.1 (h hops, c equal chunks:
+    h + c - 1)."""
+    start = link_timeline(steps)
+    return max(start) + 1 if start else 0
+
+
+def fair_order(steps: Sequence[Step]) -> List[Step]:
+    """Section 4.2.2: where trees share a link a fair scheme sends one chunk of
+    the first tree, then one chunk of the second, and so on.  The same steps
+    with the chunks of all trees taking turns: chunk 0 of every tree, then chunk
+    1 of every tree, ...; inside one (tree, chunk) the order is kept, so the
+    dependencies (which never leave a (tree, chunk)) still point backwards."""
+    order = sorted(range(len(steps)), key=lambda i: (steps[i].chunk, steps[i].tree, i))
+    new_index = {old: new for new, old in enumerate(order)}
+    return [Step(steps[i].kind, steps[i].tree, steps[i].chunk, steps[i].src, steps[i].dst, steps[i].off,
+                 steps[i].len, tuple(new_index[d] for d in steps[i].deps)) for i in order]
+
+
+def chunk_finish_times(steps: Sequence[Step]) -> Dict[Tuple[int, int], int]:
+    """(tree, chunk) -> time at which the last step of that chunk is done, under
+    link_timeline."""
+    start = link_timeline(steps)
+    out: Dict[Tuple[int, int], int] = {}
+    for s, at in zip(steps, start):
+        key = (s.tree, s.chunk)
+        out[key] = max(out.get(key, 0), at + 1)
+    return out
+
+
+def longest_idle_gap(steps: Sequence[Step], link: Tuple[int, int]) -> int:
+    """The longest time a link sits idle between two steps it carries (or before
+    its first one), under link_timeline: the "gap in the forwarding pipeline" an
+    unfair order opens downstream of a shared link (section 4.2.2)."""
+    times = sorted(at for s, at in zip(steps, link_timeline(steps)) if (s.src, s.dst) == link)
+    gaps = [times[0]] + [b - a - 1 for a, b in zip(times, times[1:])] if times else [0]
+    return max(gaps)

@@ -53,7 +53,7 @@ EXPORTS = [
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
     "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
     "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call", "blink_allreduce_noalloc",
-    "blink_schedule_set_kernel", "blink_schedule_last_kernel",
+    "blink_schedule_set_kernel", "blink_schedule_last_kernel", "blink_schedule_get_tickets",
 ]
 
 
@@ -138,6 +138,7 @@ def lib() -> C.CDLL:
     L.blink_schedule_set_wait_limit.argtypes = [vp, C.c_uint64]
     L.blink_schedule_test_skip_call.argtypes = [vp]
     L.blink_schedule_set_kernel.argtypes = [vp, C.c_int]
+    L.blink_schedule_get_tickets.argtypes = [vp, C.c_uint32, C.POINTER(C.c_uint64), vp, vp]
     L.blink_schedule_last_kernel.argtypes = [vp]
     L.blink_miad_create.argtypes = [C.c_size_t, C.c_double, C.c_size_t, C.c_size_t, C.c_size_t,
                                     C.c_double, C.POINTER(vp)]
@@ -280,6 +281,15 @@ class Schedule:
 
     def set_launch(self, wg_per_cu: int = 0, tile_elems: int = 0) -> None:
         _check(lib().blink_schedule_set_launch(self._h, wg_per_cu, tile_elems), "blink_schedule_set_launch")
+
+    def tickets(self, tile_elems: int) -> Tuple[np.ndarray, np.ndarray]:
+        """(stage, tile) per ticket, in the order the kernel hands them out."""
+        n = C.c_uint64()
+        _check(lib().blink_schedule_get_tickets(self._h, tile_elems, C.byref(n), None, None), "blink_schedule_get_tickets")
+        stage, tile = np.zeros(n.value, np.int32), np.zeros(n.value, np.int32)
+        _check(lib().blink_schedule_get_tickets(self._h, tile_elems, C.byref(n), stage.ctypes.data, tile.ctypes.data),
+               "blink_schedule_get_tickets")
+        return stage, tile
 
     def set_kernel(self, kernel: int) -> None:
         _check(lib().blink_schedule_set_kernel(self._h, kernel), "blink_schedule_set_kernel")

@@ -1,4 +1,5 @@
 // extern "C" boundary: argument checks, handle management, no exceptions out.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <memory>
@@ -185,6 +186,32 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
 blink_status_t blink_schedule_get_bounds(const blink_schedule_t* s, uint64_t* out) {
     if (!s || !out) return BLINK_EINVAL;
     for (size_t i = 0; i < s->s.bounds.size(); ++i) out[i] = s->s.bounds[i];
+    return BLINK_OK;
+}
+
+blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t tile_elems, uint64_t* n_tickets,
+                                          int32_t* stage, int32_t* tile) {
+    if (!s || !n_tickets || tile_elems < 256 || tile_elems > 65536 || (tile_elems & (tile_elems - 1))) return BLINK_EINVAL;
+    const blink::Schedule& sc = s->s;
+    unsigned shift = 0;
+    while ((1u << shift) < tile_elems) ++shift;
+    uint64_t tiles_per_chunk = 1;
+    for (const blink::StageInst& in : sc.inst)
+        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk, ((in.off + in.len + tile_elems - 1) >> shift) - (in.off >> shift));
+    const uint64_t n = static_cast<uint64_t>(sc.inst.size()) * tiles_per_chunk;
+    *n_tickets = n;
+    if (!stage && !tile) return BLINK_OK;
+    if (!stage || !tile) return BLINK_EINVAL;
+    const unsigned group = blink::ticket_group(sc);
+    for (uint64_t t = 0; t < n; ++t) {
+        unsigned ii, tt;
+        blink::ticket_to_tile(t, group, static_cast<unsigned>(tiles_per_chunk), static_cast<unsigned>(sc.inst.size()), &ii, &tt);
+        const blink::StageInst& in = sc.inst[ii];
+        const uint64_t block = (in.off >> shift) + tt;
+        const uint64_t lo = std::max<uint64_t>(in.off, block << shift), hi = std::min<uint64_t>(in.off + in.len, (block + 1) << shift);
+        stage[t] = static_cast<int32_t>(ii);
+        tile[t] = lo < hi ? static_cast<int32_t>(tt) : -1;
+    }
     return BLINK_OK;
 }
 

@@ -404,12 +404,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tiles_per_chunk = pl.tiles_per_chunk;
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
-    // Without dependencies the order of tiles is free: the trees are interleaved
-    // tile by tile (section 4.2.2), all of them while a stage reads at most 8
-    // ranks.  With more ranks per stage that makes too many request streams at a
-    // time (16 ranks x 16 one-hop trees = 256): there the trees take turns chunk
-    // by chunk (16 x 1 GiB: 5.5 -> 5.9 TB/s; two servers of 8: 5.7 -> 5.9).
-    p.group = s.has_deps || s.max_slots > 8 ? 1u : std::min(64u, std::max(1u, s.n_flows));
+    p.group = ticket_group(s);
     // Waiting waves look at their dependency every ~0.2 us in small schedules,
     // where a hand-over is most of the time (16 one-hop trees, 256 elements,
     // per-edge: 47 -> 36 us), and back off to ~0.8 us in large ones.

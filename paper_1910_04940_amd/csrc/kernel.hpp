@@ -430,12 +430,8 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
         // instances (the trees' turns at one chunk position) tickets walk tile
         // by tile across the instances, so neighbouring waves work on all trees
         // at once (section 4.2.2); group == 1 keeps an instance's tiles together.
-        const unsigned long long per_group = static_cast<unsigned long long>(group) * tiles_per_chunk;
-        const unsigned first = static_cast<unsigned>(t / per_group) * group;
-        const unsigned members = min(group, n_inst - first);
-        const unsigned within = static_cast<unsigned>(t - static_cast<unsigned long long>(first) * tiles_per_chunk);
-        const unsigned ii = first + within % members;
-        const unsigned tile = within / members;
+        unsigned ii, tile;
+        ticket_to_tile(t, group, tiles_per_chunk, n_inst, &ii, &tile);
         ConstInst in = inst + ii;
         // Tiles lie on the absolute grid of tile_elems-element blocks of the
         // payload, so tile starts are 128-byte (indeed tile-size) aligned even

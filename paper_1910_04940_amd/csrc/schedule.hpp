@@ -87,6 +87,39 @@ struct Schedule {
     uint64_t read_bytes = 0;             // the part of it that is read
 };
 
+// ---- the order in which the kernels hand out their work (section 4.2.2) ---------------
+// A ticket is (stage instance, tile).  Instances come in the schedule's
+// execution order (time slot = chunk + level, the trees taking turns inside a
+// slot); `group` consecutive instances (the trees' turns at one chunk position)
+// have their tiles handed out in turn, tile by tile across the instances, so
+// that all trees advance together; group == 1 keeps an instance's tiles
+// together.  Host and device use this one function.
+#if defined(__HIP__) || defined(__HIPCC__)
+#define BLINK_HOST_DEVICE __host__ __device__
+#else
+#define BLINK_HOST_DEVICE
+#endif
+BLINK_HOST_DEVICE inline void ticket_to_tile(unsigned long long t, unsigned group, unsigned tiles_per_chunk,
+                                             unsigned n_inst, unsigned* instance, unsigned* tile) {
+    const unsigned long long per_group = static_cast<unsigned long long>(group) * tiles_per_chunk;
+    const unsigned first = static_cast<unsigned>(t / per_group) * group;
+    const unsigned members = group < n_inst - first ? group : n_inst - first;
+    const unsigned within = static_cast<unsigned>(t - static_cast<unsigned long long>(first) * tiles_per_chunk);
+    *instance = first + within % members;
+    *tile = within / members;
+}
+
+// `group` for a schedule.  Without dependencies the order of tiles is free: the
+// trees are interleaved tile by tile, all of them while a stage reads at most 8
+// ranks.  With more ranks per stage that makes too many request streams at a
+// time (16 ranks x 16 one-hop trees = 256): there the trees take turns chunk by
+// chunk (16 x 1 GiB: 5.5 -> 5.9 TB/s; two servers of 8: 5.7 -> 5.9).  With
+// dependencies the tickets follow the execution order itself.
+inline unsigned ticket_group(const Schedule& s) {
+    if (s.has_deps || s.max_slots > 8) return 1u;
+    return s.n_flows < 1u ? 1u : (s.n_flows > 64u ? 64u : s.n_flows);
+}
+
 // Exact floor(n * (w_0+..+w_{t-1}) / (w_0+..+w_{T-1})) rounded down to a multiple of
 // `align`, made monotone; b_0 = 0, b_T = n.
 std::vector<uint64_t> split_by_weight(uint64_t n, const std::vector<double>& w, uint64_t align);

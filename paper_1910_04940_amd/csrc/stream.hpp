@@ -97,12 +97,8 @@ struct Resolver {
         Tile out;
         out.tlen = 0;
         while (t < tickets.n_items) {
-            const unsigned long long per_group = static_cast<unsigned long long>(group) * tiles_per_chunk;
-            const unsigned first = static_cast<unsigned>(t / per_group) * group;
-            const unsigned members = min(group, n_inst - first);
-            const unsigned within = static_cast<unsigned>(t - static_cast<unsigned long long>(first) * tiles_per_chunk);
-            const unsigned ii = first + within % members;
-            const unsigned tile = within / members;
+            unsigned ii, tile;
+            ticket_to_tile(t, group, tiles_per_chunk, n_inst, &ii, &tile);
             ConstInst in = inst + ii;
             const unsigned long long off = in->off, end = off + in->len;
             const unsigned long long block = (off >> tile_shift) + tile;

@@ -127,20 +127,27 @@ def connected_allocations(top: Topology, sizes: Sequence[int] = (3, 4, 5, 6, 7, 
     return out
 
 
-def count_distinct_allocations(top: Topology, subsets: Sequence[Tuple[int, ...]]) -> int:
-    """Number of subsets up to relabelling (same links with the same capacities):
-    smallest capacity matrix over all vertex orders (brute force, <= 8 vertices)."""
+def distinct_allocations(top: Topology, subsets: Sequence[Tuple[int, ...]]) -> List[Tuple[int, ...]]:
+    """One subset (the first in the given order) of every class of subsets that
+    are equal up to relabelling (same links with the same capacities): the
+    class is named by the smallest capacity matrix over all vertex orders
+    (brute force, <= 8 vertices)."""
     import itertools
     cap = {(int(u), int(v)): float(c) for u, v, c in zip(top.src, top.dst, top.cap)}
-    forms = set()
+    forms = {}
     for sub in subsets:
         best = None
         for perm in itertools.permutations(sub):
             key = tuple(cap.get((perm[i], perm[j]), 0.0) for i in range(len(sub)) for j in range(i + 1, len(sub)))
             if best is None or key < best:
                 best = key
-        forms.add((len(sub), best))
-    return len(forms)
+        forms.setdefault((len(sub), best), sub)
+    return list(forms.values())
+
+
+def count_distinct_allocations(top: Topology, subsets: Sequence[Tuple[int, ...]]) -> int:
+    """Number of subsets up to relabelling."""
+    return len(distinct_allocations(top, subsets))
 
 
 def induced(top: Topology, ranks: Sequence[int]) -> Topology:

@@ -1,6 +1,6 @@
-"""The C ABI used from plain C: a C99 program is compiled against
-include/blink.h, linked with the built library and run (host-side calls only,
-no GPU needed)."""
+"""The C ABI used from plain C: C99 programs are compiled against
+include/blink.h, linked with the built library and run: one makes host-side
+calls only (no GPU needed), one runs collectives on the GPU."""
 import importlib.util
 import os
 import shutil
@@ -43,3 +43,19 @@ def test_c_program_calls_the_host_side_entry_points(tmp_path):
     assert got[11:13] == ["copied_into_rank3", "1048576"]
     assert got[13:16] == ["split", "200.0", "500.0"]
     assert got[16:] == ["bad", "1"]          # chunk 0 -> BLINK_EINVAL
+
+
+@pytest.mark.gpu
+def test_c_program_runs_collectives_on_the_gpu(tmp_path):
+    """tests/c/abi_gpu.c: hipMalloc'ed buffers, pack -> schedule -> allreduce /
+    allreduce_noalloc / broadcast -> copy back, compared in C with the closed
+    form of an integer sum.  A fresh child process with the system HIP runtime."""
+    hip = "/opt/rocm/lib/libamdhip64.so"
+    assert os.path.exists(LIB) and os.path.exists(hip) and shutil.which("gcc")
+    exe = tmp_path / "abi_gpu"
+    subprocess.run(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c", "abi_gpu.c"), "-o", str(exe), LIB, hip,
+                    "-Wl,-rpath," + os.path.dirname(hip) + ",-rpath," + os.path.dirname(LIB)], check=True)
+    done = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert done.returncode == 0, done.stderr
+    assert done.stdout.split() == ["ok", str(5 * 4 * 1000003)]
