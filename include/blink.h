@@ -243,6 +243,12 @@ blink_status_t blink_hybrid_split(double d_total, double bw_slow, double bw_fast
 size_t blink_schedule_num_steps(const blink_schedule_t* s);   /* tree-edge transfers */
 size_t blink_schedule_num_stages(const blink_schedule_t* s);  /* passes the kernel makes (== steps for EDGE) */
 int blink_schedule_num_trees(const blink_schedule_t* s);
+/* Chunks of a tree that share a time slot of the step list.  The list is ordered
+ * by time slots of a fully pipelined execution in which the chunks advance from
+ * one tree level to the next in batches of this many; inside a slot the trees
+ * take turns chunk by chunk (section 4.2.2).  1 for short schedules; more where
+ * the kernel's waves would otherwise outrun the dependencies (many small chunks). */
+uint64_t blink_schedule_batch(const blink_schedule_t* s);
 /* out[num_steps] (host, caller-allocated): the step list in execution order. */
 blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t* out);
 /* out[num_stages] (host, caller-allocated): the kernel's passes in the order
@@ -315,7 +321,7 @@ blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtyp
  * of fixed size that is part of the library's device image (4 MiB, held by
  * every GPU the library has run on until the process ends).  Limit: the
  * schedule's block, 256 bytes + 312 bytes per stage (blink_schedule_num_stages)
- * + 88 bytes per distinct stage shape + 4 KiB, must fit into it, which allows
+ * + 124 bytes per distinct stage shape + 4 KiB, must fit into it, which allows
  * about 13,000 stages (the per-edge program of 8 ranks x 256 MiB in 1 MiB
  * chunks has 3,584); BLINK_ELIMIT otherwise, and nothing is launched.
  * All calls of this function on one GPU share the block, whichever schedule

@@ -53,7 +53,7 @@ EXPORTS = [
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
     "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
     "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call", "blink_allreduce_noalloc",
-    "blink_schedule_set_kernel", "blink_schedule_last_kernel", "blink_schedule_get_tickets",
+    "blink_schedule_set_kernel", "blink_schedule_last_kernel", "blink_schedule_get_tickets", "blink_schedule_batch",
 ]
 
 
@@ -122,6 +122,8 @@ def lib() -> C.CDLL:
     L.blink_schedule_num_stages.argtypes = [vp]
     L.blink_schedule_num_stages.restype = C.c_size_t
     L.blink_schedule_num_trees.argtypes = [vp]
+    L.blink_schedule_batch.argtypes = [vp]
+    L.blink_schedule_batch.restype = C.c_uint64
     L.blink_schedule_get_steps.argtypes = [vp, vp]
     L.blink_schedule_get_bounds.argtypes = [vp, C.POINTER(C.c_uint64)]
     L.blink_schedule_traffic_bytes.argtypes = [vp]
@@ -258,6 +260,10 @@ class Schedule:
     @property
     def num_trees(self) -> int:
         return lib().blink_schedule_num_trees(self._h)
+
+    @property
+    def batch(self) -> int:
+        return lib().blink_schedule_batch(self._h)
 
     @property
     def traffic_bytes(self) -> int:

@@ -147,6 +147,7 @@ blink_status_t blink_hybrid_split(double d_total, double bw_slow, double bw_fast
 size_t blink_schedule_num_steps(const blink_schedule_t* s) { return s ? s->s.steps.size() : 0; }
 size_t blink_schedule_num_stages(const blink_schedule_t* s) { return s ? s->s.inst.size() : 0; }
 int blink_schedule_num_trees(const blink_schedule_t* s) { return s ? s->s.n_trees : -1; }
+uint64_t blink_schedule_batch(const blink_schedule_t* s) { return s ? s->s.batch : 0; }
 
 blink_status_t blink_schedule_get_steps(const blink_schedule_t* s, blink_step_t* out) {
     if (!s || (!out && !s->s.steps.empty())) return BLINK_EINVAL;

@@ -186,7 +186,15 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
                 return BLINK_EHIP;
             }
         }
-        while (tile > kMinTile && work / tile < static_cast<uint64_t>(occ) * h->n_cu / 2) tile /= 2;
+        // Where stages wait for one another only one time slot's worth of the
+        // work can run at a time: the tile shrinks until a slot has about 64
+        // tiles, not until half the machine has one (waves beyond what a slot
+        // can use do nothing but poll: 4 ranks x 64 Ki elements per edge,
+        // 42 -> see the measurements).
+        if (s.has_deps)
+            while (tile > kMinTile && work / s.n_slots / tile < 64) tile /= 2;
+        else
+            while (tile > kMinTile && work / tile < static_cast<uint64_t>(occ) * h->n_cu / 2) tile /= 2;
     }
     // The streaming kernel (stream.hpp) takes schedules without dependencies all
     // of whose stages have a stack program within its limits.
@@ -372,8 +380,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     int per_cu = std::min(occ, direct ? 2 : (pl.read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2));
     if (h->wg_per_cu > 0) per_cu = std::min(occ, h->wg_per_cu);
     if (pl.wide && h->wg_per_cu == 0) per_cu = occ;
-    const unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
+    unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
     const unsigned long long n_items = pl.n_items;
+    // with dependencies no more waves than three time slots' worth of tickets can be busy
+    if (s.has_deps) max_grid = std::min(max_grid, std::max<unsigned long long>(64, 3 * (n_items / s.n_slots + 1)));
     const unsigned long long grid = std::min<unsigned long long>(max_grid, n_items);
 
     KParams p{};

@@ -301,16 +301,32 @@ struct Flow {
 };
 
 struct Built {
+    uint64_t batch = 1;            // chunks per flow and time slot
+    uint64_t n_slots = 1;          // time slots in use
     std::vector<StageTmpl> tmpl;
     std::vector<StageInst> inst;
     std::vector<InstWhere> where;  // per instance: tree, chunk, flow
 };
 
 // Lay the stages of all flows and chunks out in execution order.  A stage of
-// level l on chunk c gets time slot c + l, the slot in which a fully pipelined
-// execution would run it; inside a slot the flows take turns (section 4.2.2:
-// trees sharing the machine alternate chunk by chunk instead of one running
-// ahead).  Dependencies always sit in an earlier slot.
+// level l on chunk c gets time slot c / B + l: chunks advance through the levels
+// in batches of B, a fully pipelined execution with B chunks per stage and time
+// step; inside a slot the older chunks come first and, chunk by chunk, the
+// flows take turns (section 4.2.2: trees sharing the machine alternate chunk by
+// chunk instead of one running ahead).  Dependencies always sit in an earlier
+// slot.
+//
+// B.  Tickets are drawn in this order by hundreds of waves at once, so whatever
+// a ticket waits for should lie further back than the waves reach, or most of
+// them wait: B is chosen so that a slot holds about kSlotTickets tickets (with
+// B = 1 and 64 KiB chunks a slot of the 8-rank per-edge program has 112 tickets
+// and 768 waves crowd into seven slots' worth of dependencies: 3.1 ms for
+// 8 x 256 MiB; with B = 10: see the measurements), but no more chunks than keep
+// what one slot hands to the next within reach of the memory-side cache.
+constexpr uint64_t kSlotTickets = 2048;
+constexpr uint64_t kSlotElems = (64ull << 20) / 4;   // elements in flight between two slots
+constexpr uint64_t kTicketElemsGuess = 8192;         // a ticket of a schedule with dependencies
+
 Built instantiate(const std::vector<std::vector<StageTmpl>>& per_flow, const std::vector<Flow>& flows,
                   uint64_t chunk) {
     Built b;
@@ -322,13 +338,26 @@ Built instantiate(const std::vector<std::vector<StageTmpl>>& per_flow, const std
     std::vector<Key> keys;
     std::vector<size_t> tmpl_base(per_flow.size());
     std::vector<uint64_t> n_chunks(per_flow.size());
+    uint64_t stages_per_chunk_step = 0, longest = 0;
+    for (size_t f = 0; f < per_flow.size(); ++f) {
+        stages_per_chunk_step += per_flow[f].size();
+        longest = std::max(longest, flows[f].hi - flows[f].lo);
+    }
+    const uint64_t chunk_len = std::min(chunk, std::max<uint64_t>(longest, 1));
+    const uint64_t tickets_per_chunk_step =
+        std::max<uint64_t>(1, stages_per_chunk_step) * ((chunk_len + kTicketElemsGuess - 1) / kTicketElemsGuess);
+    const uint64_t by_tickets = (kSlotTickets + tickets_per_chunk_step - 1) / tickets_per_chunk_step;
+    const uint64_t by_cache = kSlotElems / std::max<uint64_t>(1, stages_per_chunk_step * chunk_len);
+    const uint64_t most_chunks = std::max<uint64_t>(1, (longest + chunk - 1) / chunk);
+    const uint64_t batch = std::max<uint64_t>(1, std::min({by_tickets, by_cache, most_chunks}));
+    b.batch = batch;
     for (size_t f = 0; f < per_flow.size(); ++f) {
         tmpl_base[f] = b.tmpl.size();
         b.tmpl.insert(b.tmpl.end(), per_flow[f].begin(), per_flow[f].end());
         n_chunks[f] = (flows[f].hi - flows[f].lo + chunk - 1) / chunk;
         for (uint64_t c = 0; c < n_chunks[f]; ++c)
             for (size_t j = 0; j < per_flow[f].size(); ++j)
-                keys.push_back({c + per_flow[f][j].level, static_cast<int>(f), static_cast<int>(j), c});
+                keys.push_back({c / batch + per_flow[f][j].level, static_cast<int>(f), static_cast<int>(j), c});
     }
     std::stable_sort(keys.begin(), keys.end(), [](const Key& a, const Key& b2) {
         if (a.slot != b2.slot) return a.slot < b2.slot;
@@ -336,6 +365,7 @@ Built instantiate(const std::vector<std::vector<StageTmpl>>& per_flow, const std
         if (a.flow != b2.flow) return a.flow < b2.flow;
         return a.local < b2.local;
     });
+    b.n_slots = keys.empty() ? 1 : keys.back().slot + 1;
     // position of (flow, chunk, local) in the order
     std::vector<std::vector<int32_t>> pos(per_flow.size());
     for (size_t f = 0; f < per_flow.size(); ++f) pos[f].assign(n_chunks[f] * per_flow[f].size(), -1);
@@ -439,12 +469,15 @@ void finish(const std::vector<Flow>& flows, std::vector<Flow> fused_flows, blink
         s.off = in.off;
         s.len = in.len;
     }
+    out.batch = e.batch;
+    out.n_slots = e.n_slots;
     if (fusion == BLINK_FUSE_EDGE) {
         out.tmpl = std::move(e.tmpl);
         out.inst = std::move(e.inst);
         out.inst_where = std::move(e.where);
     } else {
         Built f = instantiate(fused, ff, chunk);
+        out.n_slots = f.n_slots;
         out.tmpl = std::move(f.tmpl);
         out.inst = std::move(f.inst);
         out.inst_where = std::move(f.where);

@@ -75,6 +75,8 @@ struct Schedule {
     blink_op_t op = BLINK_OP_ALLREDUCE;
     blink_fusion_t fusion = BLINK_FUSE_EDGE;
     uint64_t n = 0, chunk = 0;
+    uint64_t batch = 1;                  // chunks per tree that share a time slot of the step list (see instantiate)
+    uint64_t n_slots = 1;                // time slots of the stage list (its stages, not the step list's)
     std::vector<uint64_t> bounds;        // T+1 share boundaries
     std::vector<blink_step_t> steps;     // public tree-edge step list, execution order
     std::vector<StageTmpl> tmpl;

@@ -98,14 +98,19 @@ def test_library_step_list_on_the_papers_example_is_fair():
 @pytest.mark.parametrize("coll", [bl.BLINK_OP_BROADCAST, bl.BLINK_OP_ALLREDUCE])
 def test_library_step_list_shares_every_link_chunk_by_chunk(coll):
     """On every directed link, among transfers at the same position in their
-    trees, no tree sends chunk c + 1 before every tree using that link there has
-    sent chunk c."""
+    trees, no tree sends a chunk of the next batch before every tree using that
+    link there has sent its chunks of this one, and inside a batch the trees
+    alternate chunk by chunk wherever they are at the same stage of their
+    pipelines (a batch is blink_schedule_batch chunks: 1 unless the schedule has
+    many small chunks)."""
     for top, root in ((si.hybrid_cube_mesh(), 0), (si.hybrid_cube_mesh(True), 3), (si.complete_graph(8), 2)):
         trees = bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, root)
         roots, parents, w = trees.as_lists()
         n = trees.count * 6 * 512
         sched = bl.blink_make_schedule(trees, coll, n, 512, bl.BLINK_FUSE_EDGE)
         steps = sched.steps()
+        batch = sched.batch
+        assert 1 <= batch <= 6
         depth = []
         for p in parents:
             d = [0] * top.k
@@ -122,7 +127,11 @@ def test_library_step_list_shares_every_link_chunk_by_chunk(coll):
             per_link.setdefault((int(s["src"]), int(s["dst"]), level), []).append((int(s["chunk"]), t))
         shared = 0
         for key, seq in per_link.items():
-            assert seq == sorted(seq), f"link {key}: {seq[:8]}"
+            by_batch = [(c // batch, t) for c, t in seq]
+            assert [b for b, _ in by_batch] == sorted(b for b, _ in by_batch), f"link {key}: {seq[:8]}"
+            for t in {t for _, t in seq}:
+                own = [c for c, tt in seq if tt == t]
+                assert own == sorted(own), f"link {key}, tree {t}: its own chunks out of order"
             shared += len({t for _, t in seq}) > 1
         if top.name.startswith("hybrid") and coll == bl.BLINK_OP_BROADCAST and root == 0:
             assert shared > 0, "the cube-mesh trees from one root do share first-hop links"

@@ -250,15 +250,17 @@ def test_schedule_passes_oracle_validators(top, root, n, chunk, coll, fusion):
 
 
 def test_trees_advance_together_in_the_step_order():
-    """Fair interleaving (section 4.2.2): in execution order no tree is ever more
-    than one pipeline slot ahead of another."""
+    """Fair interleaving (section 4.2.2): in execution order the chunk any tree
+    works on is never further from another tree's than the pipeline is deep,
+    counted in batches of chunks (tests/test_fair_order.py holds the order to
+    the finer properties)."""
     trees = pack(si.hybrid_cube_mesh(), 0)
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, 1 << 22, 1 << 16, bl.BLINK_FUSE_EDGE)
     seen = {}
     for s in sched.steps():
         seen[int(s["tree"])] = int(s["chunk"])
         if len(seen) == trees.count:
-            assert max(seen.values()) - min(seen.values()) <= 4   # tree height bounds the skew
+            assert max(seen.values()) - min(seen.values()) <= 5 * sched.batch   # tree height 4: five levels in flight
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_BROADCAST, 1 << 22, 1 << 16, bl.BLINK_FUSE_TREE)
     # fully fused: stage i belongs to tree i mod T
     assert sched.num_stages == trees.count * 16

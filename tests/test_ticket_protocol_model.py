@@ -102,7 +102,7 @@ def test_the_model_does_detect_a_deadlock():
     """Hand every wave to a counter it does not own (so a counter has no waves of
     its own) and starve the rest: the protocol's precondition, at least as many
     waves as counters, is what the run above depends on."""
-    inst = instances(si.chain(4), 0, 8_192, 1_024, 1_024)
+    inst = instances(si.chain(4), 0, 1_024, 1_024, 1_024)     # one chunk: every ticket waits for the one before it
     tiles_per_chunk = max(t for t, _ in inst)
     # two counters, ONE wave that never leaves counter 1: ticket 0 (counter 0) is never drawn
     counter, done = [0, 0], [0] * len(inst)
