@@ -207,28 +207,97 @@ struct Policy {
                                                            : kPolicyStream;
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t rank_window(ConstParams p, unsigned rank,
+// The rank buffers' addresses live in a vector register pair, lane r holding rank
+// r's (loaded once per wave): a rank's pointer is then one readlane away instead
+// of a scalar load that depends on another scalar load (the rank's number from
+// the stage's table), twice per rank and sub-tile.
+struct RankTable {
+    unsigned lo, hi;
+};
+__device__ __forceinline__ RankTable load_rank_table(ConstParams p, int lane) {
+    const unsigned long long mine = reinterpret_cast<unsigned long long>(p->buf[lane & (BLINK_MAX_RANKS - 1)]);
+    return {static_cast<unsigned>(mine), static_cast<unsigned>(mine >> 32)};
+}
+__device__ __forceinline__ unsigned long long rank_base(RankTable t, unsigned rank) {
+    const unsigned lo = __builtin_amdgcn_readlane(t.lo, rank);
+    const unsigned hi = __builtin_amdgcn_readlane(t.hi, rank);
+    return (static_cast<unsigned long long>(hi) << 32) | lo;
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rank_window(RankTable t, unsigned rank,
                                                               unsigned long long byte_off, unsigned bytes) {
-    char* base = reinterpret_cast<char*>(reinterpret_cast<unsigned long long>(p->buf[rank]) + byte_off);
+    char* base = reinterpret_cast<char*>(rank_base(t, rank) + byte_off);
     return __builtin_amdgcn_make_buffer_rsrc(base, 0, static_cast<int>(bytes), kRawDword3);
+}
+
+// The micro-program of a stage over the LDS slots of one sub-tile, U columns per
+// lane.  All LDS reads of an operation are issued before the first is used, and
+// the sum, by far the most common operator, has a loop of its own: with the
+// operator dispatched per column inside one loop the compiler emitted a chain
+// of branches and a full wait after every single column read.
+// The operations come off a shift register that holds the whole program
+// (fetched with two wide scalar loads per tile), not from memory one by one.
+template <typename T, int U, bool SUM>
+__device__ __forceinline__ void run_program(U4* __restrict__ slots, const unsigned long long (&prog)[5], int n_op,
+                                            unsigned redop, int lane, U4 (&acc)[U]) {
+    unsigned long long q0 = prog[0], q1 = prog[1], q2 = prog[2], q3 = prog[3], q4 = prog[4];
+    for (int o = 0; o < n_op; ++o) {
+        const unsigned code = static_cast<unsigned>(q0) & 0xffu;
+        q0 = (q0 >> 8) | (q1 << 56);
+        q1 = (q1 >> 8) | (q2 << 56);
+        q2 = (q2 >> 8) | (q3 << 56);
+        q3 = (q3 >> 8) | (q4 << 56);
+        q4 >>= 8;
+        U4* sl = slots + (code & 63u) * (U * kLanes) + lane;
+        const unsigned kind = code >> 6;
+        if (kind == OP_ST) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
+            continue;
+        }
+        U4 in[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) in[u] = sl[u * kLanes];
+        if (kind == OP_LD) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u] = in[u];
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if constexpr (!SUM)
+                    acc[u] = combine4<T>(redop, acc[u], in[u]);
+                else if constexpr (std::is_same<T, float>::value)
+                    acc[u] = __builtin_bit_cast(U4, __builtin_bit_cast(F4, acc[u]) + __builtin_bit_cast(F4, in[u]));
+                else
+                    acc[u] = acc[u] + in[u];
+            }
+        }
+    }
 }
 
 // Phases 1-3 over `bytes` bytes (a multiple of 16) at byte_off for a stage that
 // reads N ranks, U columns per lane and sub-tile.
 template <typename T, int N, int U, int LD, int ST>
-__device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+__device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, RankTable ranks, ConstTmpl st,
                                         unsigned long long byte_off, unsigned bytes, int lane) {
     constexpr unsigned kSubBytes = kLanes * U * 16;
     const unsigned redop = p->redop;
     const int n_op = BLINK_TMPL(st, n_op, 0);
     const int n_store = BLINK_TMPL(st, n_store, 0);
+    const BLINK_CONST uint32_t* w = reinterpret_cast<const BLINK_CONST uint32_t*>(st);
+    constexpr unsigned kOpWord = offsetof(StageTmpl, op) / 4;
+    static_assert(offsetof(StageTmpl, op) % 8 == 0 && kMaxOps == 40, "the micro-program is fetched as five 64-bit words");
+    unsigned long long prog[5];
+#pragma unroll
+    for (int q = 0; q < 5; ++q)
+        prog[q] = static_cast<unsigned long long>(w[kOpWord + 2 * q]) |
+                  (static_cast<unsigned long long>(w[kOpWord + 2 * q + 1]) << 32);
     for (unsigned b = 0; b < bytes; b += kSubBytes) {
         const unsigned left = bytes - b;
         // phase 1: issue every load, then park the values in LDS
         U4 r[N][U];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off + b, left);
+            const __amdgpu_buffer_rsrc_t win = rank_window(ranks, BLINK_TMPL(st, load_rank, i), byte_off + b, left);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 r[i][u] = __builtin_amdgcn_raw_buffer_load_b128(win, (u * kLanes + lane) * 16, 0, LD);
@@ -239,24 +308,13 @@ __device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, C
             for (int u = 0; u < U; ++u) slots[(i * U + u) * kLanes + lane] = r[i][u];
         // phase 2: the stage's micro-program
         U4 acc[U];
-        for (int o = 0; o < n_op; ++o) {
-            const unsigned code = BLINK_TMPL(st, op, o);
-            U4* sl = slots + (code & 63u) * (U * kLanes) + lane;
-            const unsigned kind = code >> 6;
-            if (kind == OP_LD) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] = sl[u * kLanes];
-            } else if (kind == OP_ADD) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] = combine4<T>(redop, acc[u], sl[u * kLanes]);
-            } else {
-#pragma unroll
-                for (int u = 0; u < U; ++u) sl[u * kLanes] = acc[u];
-            }
-        }
+        if (redop == BLINK_SUM)
+            run_program<T, U, true>(slots, prog, n_op, redop, lane, acc);
+        else
+            run_program<T, U, false>(slots, prog, n_op, redop, lane, acc);
         // phase 3: stores
         for (int j = 0; j < n_store; ++j) {
-            const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off + b, left);
+            const __amdgpu_buffer_rsrc_t win = rank_window(ranks, BLINK_TMPL(st, store_rank, j), byte_off + b, left);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 __builtin_amdgcn_raw_buffer_store_b128(acc[u], win, (u * kLanes + lane) * 16, 0, ST);
@@ -267,26 +325,26 @@ __device__ __forceinline__ void run_vec(U4* __restrict__ slots, ConstParams p, C
 // Pick U for a stage that reads N ranks: the largest power of two (at most 16)
 // with N * U <= COLS that does not exceed the tile (cols = tile columns per lane).
 template <typename T, int N, int COLS, int LD, int ST>
-__device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+__device__ __forceinline__ void run_vec_n(U4* __restrict__ slots, ConstParams p, RankTable ranks, ConstTmpl st,
                                           unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
     constexpr int kFit = COLS / N;
     constexpr int kBudget = kFit >= 16 ? 16 : (kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1)));
     if constexpr (kBudget >= 16)
-        if (cols >= 16) return run_vec<T, N, 16, LD, ST>(slots, p, st, byte_off, bytes, lane);
+        if (cols >= 16) return run_vec<T, N, 16, LD, ST>(slots, p, ranks, st, byte_off, bytes, lane);
     if constexpr (kBudget >= 8)
-        if (cols >= 8) return run_vec<T, N, 8, LD, ST>(slots, p, st, byte_off, bytes, lane);
+        if (cols >= 8) return run_vec<T, N, 8, LD, ST>(slots, p, ranks, st, byte_off, bytes, lane);
     if constexpr (kBudget >= 4)
-        if (cols >= 4) return run_vec<T, N, 4, LD, ST>(slots, p, st, byte_off, bytes, lane);
+        if (cols >= 4) return run_vec<T, N, 4, LD, ST>(slots, p, ranks, st, byte_off, bytes, lane);
     if constexpr (kBudget >= 2)
-        if (cols >= 2) return run_vec<T, N, 2, LD, ST>(slots, p, st, byte_off, bytes, lane);
-    run_vec<T, N, 1, LD, ST>(slots, p, st, byte_off, bytes, lane);
+        if (cols >= 2) return run_vec<T, N, 2, LD, ST>(slots, p, ranks, st, byte_off, bytes, lane);
+    run_vec<T, N, 1, LD, ST>(slots, p, ranks, st, byte_off, bytes, lane);
 }
 
 template <typename T, int COLS, int LD, int ST>
-__device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams p, ConstTmpl st,
+__device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams p, RankTable ranks, ConstTmpl st,
                                             unsigned long long byte_off, unsigned bytes, unsigned cols, int lane) {
     switch (BLINK_TMPL(st, n_load, 0)) {
-#define BLINK_CASE(N) case N: run_vec_n<T, N, COLS, LD, ST>(slots, p, st, byte_off, bytes, cols, lane); break;
+#define BLINK_CASE(N) case N: run_vec_n<T, N, COLS, LD, ST>(slots, p, ranks, st, byte_off, bytes, cols, lane); break;
         BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
         BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
         BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
@@ -299,11 +357,11 @@ __device__ __forceinline__ void run_vec_any(U4* __restrict__ slots, ConstParams 
 // whose length is not a multiple of 4 elements, and chunks that do not start on
 // a 16-byte boundary.  Slow path; one element per lane.
 template <typename T, int LD, int ST>
-__device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstParams p, ConstTmpl st,
+__device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstParams p, RankTable ranks, ConstTmpl st,
                                            unsigned long long byte_off, unsigned bytes, int lane) {
     const int n_load = BLINK_TMPL(st, n_load, 0);
     for (int i = 0; i < n_load; ++i) {
-        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, load_rank, i), byte_off, bytes);
+        const __amdgpu_buffer_rsrc_t win = rank_window(ranks, BLINK_TMPL(st, load_rank, i), byte_off, bytes);
         slots[i * kLanes + lane] = __builtin_amdgcn_raw_buffer_load_b32(win, lane * 4, 0, LD);
     }
     unsigned acc = 0;
@@ -322,7 +380,7 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
     }
     const int n_store = BLINK_TMPL(st, n_store, 0);
     for (int j = 0; j < n_store; ++j) {
-        const __amdgpu_buffer_rsrc_t win = rank_window(p, BLINK_TMPL(st, store_rank, j), byte_off, bytes);
+        const __amdgpu_buffer_rsrc_t win = rank_window(ranks, BLINK_TMPL(st, store_rank, j), byte_off, bytes);
         __builtin_amdgcn_raw_buffer_store_b32(acc, win, lane * 4, 0, ST);
     }
 }
@@ -348,6 +406,7 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     constexpr int ST = Policy<FLAVOUR>::kStore;
     const int lane = threadIdx.x;
     ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
+    const RankTable ranks = load_rank_table(p, lane);
     unsigned long long* const ticket = p->ticket;
     unsigned long long* const done = p->done;
     ConstTmpl const tmpl = reinterpret_cast<ConstTmpl>(reinterpret_cast<unsigned long long>(p->tmpl));
@@ -491,15 +550,15 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
             const unsigned long long e0 = lo_e;  // first element of the tile
             if ((e0 & 3ull) == 0) {
                 const unsigned vec_bytes = (tlen >> 2) * 16u;
-                if (vec_bytes) run_vec_any<T, COLS, LD, ST>(slots, p, st, e0 * 4ull, vec_bytes, cols, lane);
+                if (vec_bytes) run_vec_any<T, COLS, LD, ST>(slots, p, ranks, st, e0 * 4ull, vec_bytes, cols, lane);
                 const unsigned rem = tlen & 3u;  // only where the payload itself ends off a 16-byte boundary
                 if (rem)
-                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + vec_bytes,
+                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, ranks, st, e0 * 4ull + vec_bytes,
                                           rem * 4u, lane);
             } else {
                 // chunk size not a multiple of 4 elements: element-wise, slow but correct
                 for (unsigned b = 0; b < tlen * 4u; b += kLanes * 4u)
-                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, e0 * 4ull + b,
+                    run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, ranks, st, e0 * 4ull + b,
                                           min(static_cast<unsigned>(kLanes) * 4u, tlen * 4u - b), lane);
             }
 

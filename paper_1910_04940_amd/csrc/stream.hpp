@@ -137,13 +137,6 @@ struct Resolver {
     }
 };
 
-// Rank r's buffer address, from the table the lanes hold (lane r: rank r).
-__device__ __forceinline__ unsigned long long rank_base(unsigned buf_lo, unsigned buf_hi, unsigned rank) {
-    const unsigned lo = __builtin_amdgcn_readlane(buf_lo, rank);
-    const unsigned hi = __builtin_amdgcn_readlane(buf_hi, rank);
-    return (static_cast<unsigned long long>(hi) << 32) | lo;
-}
-
 // s_waitcnt vmcnt(n): at most n of this wave's vector memory operations are
 // still outstanding (they complete in the order in which they were issued).
 template <int N>
@@ -239,7 +232,7 @@ __device__ __forceinline__ void run_stack(const U4* __restrict__ slots, const ui
 // at element cur.first.  Draws and resolves the wave's next ticket while the
 // tile's first loads are in flight, and returns it.
 template <typename T, int N, int LD, int ST>
-__device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, unsigned buf_lo, unsigned buf_hi,
+__device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, RankTable ranks,
                                             const Tile& cur, unsigned bytes, int lane, Resolver& res) {
     constexpr int U = N <= 4 ? 16 : (N <= 8 ? 8 : 4);  // N * U <= kColumnsDirect
     // a stack program over N ranks needs at most N / 2 accumulators; schedules
@@ -258,7 +251,7 @@ __device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, unsigned buf
         for (int i = 0; i < N; ++i) {
             const unsigned rank = (cur.seq_ranks[i / 4] >> ((i & 3) * 8)) & 0xffu;
             const __amdgpu_buffer_rsrc_t win = __builtin_amdgcn_make_buffer_rsrc(
-                reinterpret_cast<char*>(rank_base(buf_lo, buf_hi, rank) + byte_off + b), 0, static_cast<int>(left),
+                reinterpret_cast<char*>(rank_base(ranks, rank) + byte_off + b), 0, static_cast<int>(left),
                 kRawDword3);
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -286,7 +279,7 @@ __device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, unsigned buf
             if (j < n_store) {
                 const unsigned rank = (cur.store_ranks[j / 4] >> ((j & 3) * 8)) & 0xffu;
                 const __amdgpu_buffer_rsrc_t win = __builtin_amdgcn_make_buffer_rsrc(
-                    reinterpret_cast<char*>(rank_base(buf_lo, buf_hi, rank) + byte_off + b), 0,
+                    reinterpret_cast<char*>(rank_base(ranks, rank) + byte_off + b), 0,
                     static_cast<int>(left), kRawDword3);
 #pragma unroll
                 for (int u = 0; u < U; ++u)
@@ -305,10 +298,7 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
     const int lane = threadIdx.x;
     ConstParams p = (ConstParams)__builtin_amdgcn_kernarg_segment_ptr();
     if (__hip_atomic_load(p->status + kStatusState, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    // lane r keeps rank r's buffer address: rank pointers are then one readlane
-    // away, whatever order a stage names the ranks in
-    const unsigned long long mine = reinterpret_cast<unsigned long long>(p->buf[lane & (BLINK_MAX_RANKS - 1)]);
-    const unsigned buf_lo = static_cast<unsigned>(mine), buf_hi = static_cast<unsigned>(mine >> 32);
+    const RankTable ranks = load_rank_table(p, lane);
 
     Resolver res;
     res.tmpl = reinterpret_cast<ConstTmpl>(reinterpret_cast<unsigned long long>(p->tmpl));
@@ -333,7 +323,7 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
         if (vec_bytes) {
             resolved = true;
             switch (cur.n_load) {
-#define BLINK_CASE(N) case N: next = stream_tile<T, N, LD, ST>(slots, buf_lo, buf_hi, cur, vec_bytes, lane, res); break;
+#define BLINK_CASE(N) case N: next = stream_tile<T, N, LD, ST>(slots, ranks, cur, vec_bytes, lane, res); break;
                 BLINK_CASE(1) BLINK_CASE(2) BLINK_CASE(3) BLINK_CASE(4) BLINK_CASE(5) BLINK_CASE(6)
                 BLINK_CASE(7) BLINK_CASE(8) BLINK_CASE(9) BLINK_CASE(10) BLINK_CASE(11) BLINK_CASE(12)
                 BLINK_CASE(13) BLINK_CASE(14) BLINK_CASE(15) BLINK_CASE(16)
@@ -348,11 +338,11 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
         if (aligned) {
             const unsigned rem = cur.tlen & 3u;
             if (rem)
-                run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, cur.first * 4ull + vec_bytes, rem * 4u,
+                run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, ranks, st, cur.first * 4ull + vec_bytes, rem * 4u,
                                       lane);
         } else {
             for (unsigned b = 0; b < cur.tlen * 4u; b += kLanes * 4u)
-                run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, st, cur.first * 4ull + b,
+                run_scalar<T, LD, ST>(reinterpret_cast<unsigned*>(slots), p, ranks, st, cur.first * 4ull + b,
                                       min(static_cast<unsigned>(kLanes) * 4u, cur.tlen * 4u - b), lane);
         }
         if (!resolved) next = res.resolve(res.tickets.draw(lane), lane);
