@@ -61,8 +61,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=6,
-                    help="untimed calls first (a schedule's first five calls include the library's timed choice between its two kernels)")
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", choices=sorted(CONFIGS), default="headline",
                     help="benchmark configuration (default: the headline workload)")
     ap.add_argument("--fusion", choices=["edge", "node", "tree"], default="tree")
@@ -301,6 +300,14 @@ def main():
         for sched, bufs, _, m in calls:
             run(bufs, m, dtype, sched, stream.cuda_stream)
 
+    # Set-up, outside warm-up and timing like the building of the schedules: the
+    # library spends a schedule's first five calls choosing between its two
+    # kernels (four timed calls, then one that waits for them).
+    SETUP_CALLS = 5
+    restore()
+    for _ in range(SETUP_CALLS):
+        step()
+    torch.cuda.synchronize()
     since_restore = 0
     restore()
     for _ in range(args.warmup):
@@ -390,7 +397,8 @@ def main():
                    "calls_per_step": len(calls), "trees": trees.count, "fusion": args.fusion, "layout": layout,
                    "stages": sum(s.num_stages for s in scheds),
                    "steps_in_schedule": sum(s.num_steps for s in scheds),
-                   "restores_in_timed_region": restores, "commit": git_head()},
+                   "restores_in_timed_region": restores, "setup_calls_per_schedule": SETUP_CALLS,
+                   "kernel_serving": sorted({s.last_kernel for s in scheds}), "commit": git_head()},
         "roofline": roofline,
     }
 
