@@ -20,16 +20,29 @@
 //     schedule.hpp): ranks are loaded in the order in which they are consumed,
 //     rank i into LDS slot i, so every LDS address is a compile-time constant,
 //     the reads of all ranks can be scheduled ahead of the arithmetic, partial
-//     sums stay in registers (up to four accumulators), and rank i is consumed
-//     as soon as ITS loads have arrived (vector memory operations complete in
-//     order), while later ranks are still on their way.
+//     sums stay in registers (up to four accumulators).  The waits are written
+//     per rank (vector memory operations complete in order, so rank i has
+//     arrived once no more than the later ranks' loads are outstanding), but the
+//     compiler puts a wait for ALL of the wave's vector memory operations in
+//     front of the first LDS read that follows loads into LDS, whose
+//     destinations it cannot tell apart: the sum starts when the last rank is in.
 //   * The next ticket is drawn just before the tile's loads are issued and
 //     resolved (instance, tile, stage shape) while they are in flight.
 //
 // What limits it (measured per 64 KiB sub-tile of an 8-rank stage, one wave per
 // CU): issuing the 64 loads takes 2.8 us and the 64 stores 2.7 us, both at the
 // pace at which HBM takes them; the sum itself 2.0 us, during which the wave has
-// nothing in flight.  A second wave per CU fills those gaps only in part.
+// nothing in flight (most of it moves and selects: the compiler turns the
+// uniform branches on the depth into selects over all accumulators).  A second
+// wave per CU fills those gaps only in part.  Variants without these costs (LDS
+// reads as assembly so that rank i really is consumed when it arrives; only the
+// top accumulator in registers and the others parked in LDS; loads issued a
+// sub-tile ahead into two LDS halves; the ticket drawn a tile ahead) were built
+// and measured on the same machine: each made one wave per CU faster (8 ranks
+// x 256 MiB: 0.51 -> 0.75 of the HBM peak) and two waves per CU, this kernel's
+// launch, slower (0.73 -> 0.69; 6 ranks: 0.685 -> 0.65), because a lone wave is
+// bound by its own instruction issue and two fast ones crowd the memory system;
+// none beat blink_consume's 0.795, so the kernel stayed as it is.
 #pragma once
 #include <utility>
 
@@ -39,12 +52,11 @@ namespace blink {
 
 constexpr int kColumnsDirect = 64;  // LDS slots per lane: 64 KiB per wave
 
-// Accumulators a stage's stack program may have at a time: the top one in
-// registers, the others parked in LDS.  A stage over N ranks needs at most N / 2.
-constexpr int kStreamStackLevels = BLINK_MAX_RANKS / 2;
-
 using LdsPtr = __attribute__((address_space(3))) void*;
 
+// Loads that write LDS: the explicit waits before the LDS reads
+// (wait_vector_memory below) state what each read needs; the compiler adds a
+// wait of its own for all vector memory operations before the first of them.
 
 struct TicketSource {
     unsigned long long* counter;
@@ -61,25 +73,14 @@ struct TicketSource {
             raw = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return raw;
     }
-    // The answer is taken out of its vector register on every path, the dealt
-    // one included (the empty statement is a use the compiler cannot drop).  A
-    // path on which the register may still be awaiting the counter costs more
-    // than the wait it saves: wherever that register is written next, the
-    // compiler first waits for all the wave's vector memory operations, and it
-    // reuses the register in the middle of the tile loop.  (For the same reason
-    // the answer is not kept across a tile to hide the counter's latency
-    // altogether: under the tile body's register pressure the compiler moves it
-    // to another register at once, which is a wait for it at once.)
     __device__ __forceinline__ unsigned long long end_draw(unsigned long long raw) {
-        unsigned raw_lo = static_cast<unsigned>(raw), raw_hi = static_cast<unsigned>(raw >> 32);
-        asm volatile("" : "+v"(raw_lo), "+v"(raw_hi)::"memory");
-        const unsigned lo = __builtin_amdgcn_readfirstlane(raw_lo);
-        const unsigned hi = __builtin_amdgcn_readfirstlane(raw_hi);
         if (dealt) {
             const unsigned long long t = next_static;
             next_static += stride;
             return t;
         }
+        const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw));
+        const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(raw >> 32));
         return ((static_cast<unsigned long long>(hi) << 32) | lo) - base;
     }
     __device__ __forceinline__ unsigned long long draw(int lane) { return end_draw(begin_draw(lane)); }
@@ -159,132 +160,86 @@ __device__ __forceinline__ void wait_vector_memory() {
     asm volatile("" ::: "memory");  // no LDS read may be moved above the wait
 }
 
-template <typename T>
-__device__ __forceinline__ U4 column_sum(U4 a, U4 b) {
+// U columns of a lane as one value.  The accumulators are values of this type,
+// not arrays: conditional updates of values stay in registers, whereas the
+// compiler turns conditional updates of array levels selected by the depth into
+// one run-time index, and the stack would live in memory.
+template <int U>
+struct Wide {
+    typedef unsigned Bits __attribute__((ext_vector_type(4 * U)));
+    typedef float Floats __attribute__((ext_vector_type(4 * U)));
+};
+
+template <typename T, int U>
+__device__ __forceinline__ typename Wide<U>::Bits wide_sum(typename Wide<U>::Bits a, typename Wide<U>::Bits b) {
     if constexpr (std::is_same<T, float>::value)
-        return __builtin_bit_cast(U4, __builtin_bit_cast(F4, a) + __builtin_bit_cast(F4, b));
+        return __builtin_bit_cast(typename Wide<U>::Bits, __builtin_bit_cast(typename Wide<U>::Floats, a) +
+                                                              __builtin_bit_cast(typename Wide<U>::Floats, b));
     else
         return a + b;
 }
 
-// LDS access to a lane's U columns of one slot, as assembly.  `addr`: the LDS
-// address of the lane's column 0 of the slot minus OFF bytes (columns are
-// kLanes * 16 = 1024 bytes apart).
-//
-// Assembly because of what the compiler does with LDS reads it can see: it
-// tracks loads that write LDS, cannot tell their destinations apart, and puts
-// s_waitcnt vmcnt(0) in front of the first LDS read after them.  That wait
-// covers every load of the sub-tile and the previous sub-tile's stores: the wave
-// would start summing only once nothing of its own is in flight any more.  Here
-// the wait before rank i's slot is the caller's (wait_vector_memory), for that
-// rank's loads alone.  Each statement ends with lgkmcnt(0): what it read is an
-// ordinary register value to the compiler, what it wrote is in LDS.
-#define BLINK_LDS4(OPCODE, CONSTRAINT, B)                                                                     \
-    asm volatile(OPCODE " %0, %4 offset:%5\n\t" OPCODE " %1, %4 offset:%6\n\t" OPCODE " %2, %4 offset:%7\n\t" \
-                 OPCODE " %3, %4 offset:%8\n\ts_waitcnt lgkmcnt(0)"                                           \
-                 : CONSTRAINT(v[B]), CONSTRAINT(v[B + 1]), CONSTRAINT(v[B + 2]), CONSTRAINT(v[B + 3])         \
-                 : "v"(addr), "n"(OFF + (B) * 1024), "n"(OFF + (B + 1) * 1024), "n"(OFF + (B + 2) * 1024),    \
-                   "n"(OFF + (B + 3) * 1024)                                                                  \
-                 : "memory")
-#define BLINK_LDS8(OPCODE, CONSTRAINT, B)                                                                     \
-    asm volatile(OPCODE " %0, %8 offset:%9\n\t" OPCODE " %1, %8 offset:%10\n\t" OPCODE                        \
-                        " %2, %8 offset:%11\n\t" OPCODE " %3, %8 offset:%12\n\t" OPCODE                       \
-                        " %4, %8 offset:%13\n\t" OPCODE " %5, %8 offset:%14\n\t" OPCODE                       \
-                        " %6, %8 offset:%15\n\t" OPCODE " %7, %8 offset:%16\n\ts_waitcnt lgkmcnt(0)"          \
-                 : CONSTRAINT(v[B]), CONSTRAINT(v[B + 1]), CONSTRAINT(v[B + 2]), CONSTRAINT(v[B + 3]),        \
-                   CONSTRAINT(v[B + 4]), CONSTRAINT(v[B + 5]), CONSTRAINT(v[B + 6]), CONSTRAINT(v[B + 7])     \
-                 : "v"(addr), "n"(OFF + (B) * 1024), "n"(OFF + (B + 1) * 1024), "n"(OFF + (B + 2) * 1024),    \
-                   "n"(OFF + (B + 3) * 1024), "n"(OFF + (B + 4) * 1024), "n"(OFF + (B + 5) * 1024),           \
-                   "n"(OFF + (B + 6) * 1024), "n"(OFF + (B + 7) * 1024)                                       \
-                 : "memory")
-template <int U, int OFF>
-__device__ __forceinline__ void lds_read(unsigned addr, U4 (&v)[U]) {
-    static_assert(U == 4 || U == 8 || U == 16, "one statement per batch of four or eight columns");
-    static_assert(OFF >= 0 && OFF + (U - 1) * 1024 < 65536, "the offset field has 16 bits");
-    if constexpr (U == 4) {
-        BLINK_LDS4("ds_read_b128", "=&v", 0);
-    } else if constexpr (U == 8) {
-        BLINK_LDS8("ds_read_b128", "=&v", 0);
-    } else {
-        BLINK_LDS8("ds_read_b128", "=&v", 0);
-        BLINK_LDS8("ds_read_b128", "=&v", 8);
+// The U columns of LDS slot `slot` that belong to this lane.
+template <int U>
+__device__ __forceinline__ typename Wide<U>::Bits read_slot(const U4* __restrict__ slots, int slot, int lane) {
+    typename Wide<U>::Bits x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const U4 v = slots[(slot * U + u) * kLanes + lane];
+        x[4 * u] = v.x, x[4 * u + 1] = v.y, x[4 * u + 2] = v.z, x[4 * u + 3] = v.w;
     }
+    return x;
 }
-#undef BLINK_LDS4
-#undef BLINK_LDS8
-// ds_write takes the address first, then the data: statements of their own.
-#define BLINK_LDSW4(B)                                                                                      \
-    asm volatile("ds_write_b128 %0, %1 offset:%5\n\tds_write_b128 %0, %2 offset:%6\n\t"                    \
-                 "ds_write_b128 %0, %3 offset:%7\n\tds_write_b128 %0, %4 offset:%8\n\ts_waitcnt lgkmcnt(0)" \
-                 :                                                                                          \
-                 : "v"(addr), "v"(v[B]), "v"(v[B + 1]), "v"(v[B + 2]), "v"(v[B + 3]), "n"(OFF + (B) * 1024),  \
-                   "n"(OFF + (B + 1) * 1024), "n"(OFF + (B + 2) * 1024), "n"(OFF + (B + 3) * 1024)           \
-                 : "memory")
-template <int U, int OFF>
-__device__ __forceinline__ void lds_write(unsigned addr, const U4 (&v)[U]) {
-    static_assert(U == 4 || U == 8 || U == 16, "one statement per batch of four columns");
-    static_assert(OFF >= 0 && OFF + (U - 1) * 1024 < 65536, "the offset field has 16 bits");
-    BLINK_LDSW4(0);
-    if constexpr (U >= 8) BLINK_LDSW4(4);
-    if constexpr (U == 16) {
-        BLINK_LDSW4(8);
-        BLINK_LDSW4(12);
-    }
-}
-#undef BLINK_LDSW4
 
 // The stack program of a stage over the ranks in LDS slots 0 .. N-1 (slot i =
-// the i-th rank consumed, U columns per lane), with the sum as the operator.
-// Only the top accumulator of the stack lives in registers.  A rank that starts
-// a new accumulator first parks the current top in the slot of the rank
-// consumed just before it (free by then, and a compile-time address); folding
-// the top into the level below reads that level back.  `parked` holds the slots
-// of the parked levels, as scalars chosen by the (wave-uniform) depth: LDS can
-// be addressed at run time, registers cannot, and a stack of accumulators in
-// registers costs the compiler more in copies between its branches than the
-// sums themselves (per rank 150 to 200 moves and selects around 32 additions).
-// Rank i is consumed once its own loads have arrived: the loads were the wave's
-// last N * U vector memory operations.  The first code always starts an
-// accumulator (stack_program sees to that).
-template <typename T, int N, int U>
-__device__ __forceinline__ void run_stack(unsigned lane_addr, const uint32_t (&codes)[4], U4 (&top)[U]) {
-    constexpr int kSlot = U * kLanes * 16;  // bytes
-    int depth = 0;                          // accumulators below the top one
-    unsigned parked[kStreamStackLevels - 1] = {};
-    wait_vector_memory<(N - 1) * U>();
-    lds_read<U, 0>(lane_addr, top);
-#define BLINK_STACK_STEP(I)                                                                 \
-    if constexpr (I < N) {                                                                  \
-        const unsigned code = (codes[I / 4] >> ((I & 3) * 8)) & 0xffu;                      \
-        if constexpr (I > 0) {                                                              \
-            wait_vector_memory<(N - 1 - I) * U>();                                          \
-            if (code & 1u) {                                                                \
-                lds_write<U, (I - 1) * kSlot>(lane_addr, top);                              \
-                _Pragma("unroll") for (int d = 0; d < kStreamStackLevels - 1; ++d)          \
-                    if (d == depth) parked[d] = (I - 1) * kSlot;                            \
-                ++depth;                                                                    \
-                lds_read<U, I * kSlot>(lane_addr, top);                                     \
-            } else {                                                                        \
-                U4 x[U];                                                                    \
-                lds_read<U, I * kSlot>(lane_addr, x);                                       \
-                _Pragma("unroll") for (int u = 0; u < U; ++u) top[u] = column_sum<T>(top[u], x[u]); \
-            }                                                                               \
-        }                                                                                   \
-        for (unsigned f = code >> 1; f; --f) { /* the level below += the top level */       \
-            --depth;                                                                        \
-            unsigned from = parked[0];                                                      \
-            _Pragma("unroll") for (int d = 1; d < kStreamStackLevels - 1; ++d)              \
-                if (d == depth) from = parked[d];                                           \
-            U4 below[U];                                                                    \
-            lds_read<U, 0>(lane_addr + from, below);                                        \
-            _Pragma("unroll") for (int u = 0; u < U; ++u) top[u] = column_sum<T>(below[u], top[u]); \
-        }                                                                                   \
+// the i-th rank consumed), U columns per lane, with the sum as the operator and
+// up to D accumulators a0 (bottom) .. a3; `depth` (wave-uniform) is the index of
+// the top one.  Registers cannot be indexed at run time: every operation
+// branches, uniformly, on the depth.  The wait before rank i is for its own
+// loads: the loads were the wave's last N * U vector memory operations (but for
+// any issued after them, which only makes a wait longer than needed).
+template <typename T, int N, int U, int D>
+__device__ __forceinline__ void run_stack(const U4* __restrict__ slots, const uint32_t (&codes)[4], int lane,
+                                          U4 (&result)[U]) {
+    using W = typename Wide<U>::Bits;
+    W a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    int depth = -1;
+#define BLINK_STACK_STEP(I)                                                              \
+    if constexpr (I < N) {                                                               \
+        wait_vector_memory<(N - 1 - I) * U>();                                           \
+        const W x = read_slot<U>(slots, I, lane);                                        \
+        const unsigned code = (codes[I / 4] >> ((I & 3) * 8)) & 0xffu;                   \
+        if (code & 1u) {                                                                 \
+            ++depth;                                                                     \
+            if (D == 1 || depth == 0) a0 = x;                                            \
+            if (D > 1 && depth == 1) a1 = x;                                             \
+            if (D > 2 && depth == 2) a2 = x;                                             \
+            if (D > 3 && depth == 3) a3 = x;                                             \
+        } else {                                                                         \
+            if (D == 1 || depth == 0) a0 = wide_sum<T, U>(a0, x);                        \
+            if (D > 1 && depth == 1) a1 = wide_sum<T, U>(a1, x);                         \
+            if (D > 2 && depth == 2) a2 = wide_sum<T, U>(a2, x);                         \
+            if (D > 3 && depth == 3) a3 = wide_sum<T, U>(a3, x);                         \
+        }                                                                                \
+        if (D > 1)                                                                       \
+            for (unsigned f = code >> 1; f; --f) { /* the level below += the top level */ \
+                if (depth == 1) a0 = wide_sum<T, U>(a0, a1);                             \
+                if (D > 2 && depth == 2) a1 = wide_sum<T, U>(a1, a2);                    \
+                if (D > 3 && depth == 3) a2 = wide_sum<T, U>(a2, a3);                    \
+                --depth;                                                                 \
+            }                                                                            \
     }
     BLINK_STACK_STEP(0) BLINK_STACK_STEP(1) BLINK_STACK_STEP(2) BLINK_STACK_STEP(3)
     BLINK_STACK_STEP(4) BLINK_STACK_STEP(5) BLINK_STACK_STEP(6) BLINK_STACK_STEP(7)
     BLINK_STACK_STEP(8) BLINK_STACK_STEP(9) BLINK_STACK_STEP(10) BLINK_STACK_STEP(11)
     BLINK_STACK_STEP(12) BLINK_STACK_STEP(13) BLINK_STACK_STEP(14) BLINK_STACK_STEP(15)
 #undef BLINK_STACK_STEP
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        U4 v;
+        v.x = a0[4 * u], v.y = a0[4 * u + 1], v.z = a0[4 * u + 2], v.w = a0[4 * u + 3];
+        result[u] = v;
+    }
 }
 
 // The 16-byte columns of one tile of a stage that reads N ranks: `bytes` bytes
@@ -294,10 +249,12 @@ template <typename T, int N, int LD, int ST>
 __device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, RankTable ranks,
                                             const Tile& cur, unsigned bytes, int lane, Resolver& res) {
     constexpr int U = N <= 4 ? 16 : (N <= 8 ? 8 : 4);  // N * U <= kColumnsDirect
+    // a stack program over N ranks needs at most N / 2 accumulators; schedules
+    // that need more than four do not come here (see the launcher)
+    constexpr int D = N < 4 ? 1 : (N < 6 ? 2 : (N < 8 ? 3 : 4));
     constexpr unsigned kSubBytes = kLanes * U * 16;
     const unsigned long long byte_off = cur.first * 4ull;
     const int n_store = static_cast<int>(cur.n_store);
-    const unsigned lane_addr = static_cast<unsigned>(reinterpret_cast<size_t>((LdsPtr)slots)) + lane * 16u;
     Tile next;
     for (unsigned b = 0; b < bytes; b += kSubBytes) {
         const unsigned left = bytes - b;
@@ -317,13 +274,17 @@ __device__ __forceinline__ Tile stream_tile(U4* __restrict__ slots, RankTable ra
         }
         // The counter's answer arrives before the data (vector memory operations
         // complete in order); the next tile is resolved while the data travels.
-        // The empty statement in end_draw pins the answer's first use to this
-        // point of the program: without it the compiler reads it, and waits for
-        // it, before issuing the loads.
-        if (b == 0) next = res.resolve(res.tickets.end_draw(raw), lane);
+        // The empty statement pins the answer's first use to this point of the
+        // program: without it the compiler reads it, and waits for it, before
+        // issuing the loads.
+        if (b == 0) {
+            unsigned raw_lo = static_cast<unsigned>(raw), raw_hi = static_cast<unsigned>(raw >> 32);
+            asm volatile("" : "+v"(raw_lo), "+v"(raw_hi)::"memory");
+            next = res.resolve(res.tickets.end_draw((static_cast<unsigned long long>(raw_hi) << 32) | raw_lo), lane);
+        }
         // phase 2: the stage's stack program; rank i is awaited just before its turn
         U4 acc[U];
-        run_stack<T, N, U>(lane_addr, cur.seq_codes, acc);
+        run_stack<T, N, U, D>(slots, cur.seq_codes, lane, acc);
         // phase 3: stores.  The LDS reads above have all been consumed (their
         // values are in acc, which the stores take) before the next sub-tile's
         // loads, later in program order, overwrite the slots.
@@ -404,8 +365,8 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
 }
 
 // The most accumulators the stack program of a stage that reads n_load ranks may
-// need for blink_stream to run it: every stack program fits (N / 2 at most).
-inline int stream_stack_limit(int) { return kStreamStackLevels; }
+// need for blink_stream to run it (stream_tile's D).
+inline int stream_stack_limit(int n_load) { return n_load < 4 ? 1 : (n_load < 6 ? 2 : (n_load < 8 ? 3 : 4)); }
 
 // The kernel for a flavour on payloads that stream.  `direct`: the schedule has no
 // dependencies, all its stages have stack programs within the limit and the
