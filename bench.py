@@ -301,9 +301,9 @@ def main():
             run(bufs, m, dtype, sched, stream.cuda_stream)
 
     # Set-up, outside warm-up and timing like the building of the schedules: the
-    # library spends a schedule's first five calls choosing between its two
-    # kernels (four timed calls, then one that waits for them).
-    SETUP_CALLS = 5
+    # library spends a schedule's first nine calls choosing between its two
+    # kernels (eight timed calls, then one that waits for them).
+    SETUP_CALLS = 9
     restore()
     for _ in range(SETUP_CALLS):
         step()

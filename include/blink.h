@@ -343,9 +343,9 @@ blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems,
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
 /* Two kernels can run a sum over a schedule whose stages do not wait for one
  * another (whole-tree fusion) at streaming sizes; they give the same bits.
- * kernel: 0 = automatic (the first four calls of at least 64 MiB of traffic
+ * kernel: 0 = automatic (the first eight calls of at least 64 MiB of traffic
  * alternate between the two and are timed with events on the caller's stream;
- * the fifth call waits for them and the faster kernel serves from then on;
+ * the ninth call waits for them and the faster kernel serves from then on;
  * blink_allreduce_noalloc takes no part in the timing), 1 = the ticket-drawing kernel with
  * loads staged through registers, 2 = the streaming kernel with loads straight
  * into LDS.  Schedules only one of them can run are not affected.

@@ -273,7 +273,7 @@ blink_status_t read_status(blink_schedule* h, blink_progress_t* out) {
 // for the last of them (the one time a call waits for the device, besides a
 // schedule's first) and the kernel with the smaller minimum serves the rest.
 // Both give the same bits.
-constexpr int kTrialCalls = 4;
+constexpr int kTrialCalls = 8;
 constexpr uint64_t kTrialMinBytes = 64ull << 20;  // smaller calls are too short to time against one another
 
 namespace {
@@ -309,14 +309,18 @@ int choose_kernel(blink_schedule* h, bool static_block, int* timed) {
         return 1 + (h->trial_calls & 1);
     }
     // All trial calls are launched: wait for the last of them (once per
-    // schedule, at its fifth call) and compare.
+    // schedule, at its ninth call) and compare the fastest of each kernel's
+    // calls but its first (which carries what happens once: the code's first
+    // launch, tables not yet in any cache).  Kernels of a tenth of a millisecond
+    // differ by a few percent, which is also what the event pair around a single
+    // launch scatters by: hence three samples each, not one.
     float best[2] = {1e30f, 1e30f};
     bool ok = hipEventSynchronize(static_cast<hipEvent_t>(h->trial_event[2 * kTrialCalls - 1])) == hipSuccess;
     for (int c = 0; ok && c < kTrialCalls; ++c) {
         float ms = 0.f;
         ok = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(h->trial_event[2 * c]),
                                  static_cast<hipEvent_t>(h->trial_event[2 * c + 1])) == hipSuccess;
-        best[c & 1] = std::min(best[c & 1], ms);
+        if (c >= 2) best[c & 1] = std::min(best[c & 1], ms);
     }
     if (!ok) (void)hipGetLastError();
     h->picked = ok && best[1] < best[0] ? 2 : 1;

@@ -55,7 +55,7 @@ struct blink_schedule {
     int kernel_choice = 0;        // the caller's wish: 0 = pick the faster, 1 = blink_consume, 2 = blink_stream
     int picked = 0;               // the pick once made (1 or 2); 0 = not yet
     int trial_calls = 0;          // timed calls launched so far (they alternate between the two kernels)
-    void* trial_event[8] = {};    // hipEvent_t pairs around the timed calls
+    void* trial_event[16] = {};   // hipEvent_t pairs around the timed calls
     bool trial_events_made = false;
 };
 

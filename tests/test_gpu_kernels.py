@@ -122,15 +122,15 @@ def test_automatic_choice_times_both_and_settles():
     x = [si.hash_payload(23, r, 0, n, "int32") for r in range(k)]
     want = ox.allreduce_int32_definition(x)
     seen = []
-    for call in range(8):
+    for call in range(12):
         bufs = [torch.from_numpy(a).to(dev) for a in x]
         bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream)
         seen.append(sched.last_kernel)
         torch.cuda.synchronize()
         for b in bufs:
             assert np.array_equal(b.cpu().numpy(), want), call
-    assert seen[:4] == [1, 2, 1, 2]                  # the timed calls alternate
-    assert len(set(seen[4:])) == 1 and seen[4] in (1, 2)   # then one kernel serves
+    assert seen[:8] == [1, 2] * 4                    # the timed calls alternate
+    assert len(set(seen[8:])) == 1 and seen[8] in (1, 2)   # then one kernel serves
     # a small payload is not worth a trial
     m = 1 << 12
     small = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, m, 1 << 10, bl.BLINK_FUSE_TREE)
