@@ -278,9 +278,12 @@ void blink_schedule_free(blink_schedule_t* s);
 
 /* bufs: HOST array of k DEVICE pointers; each buffer holds at least n_elems
  * 4-byte elements, is 16-byte aligned and overlaps no other.  In place.
- * (Performance only: buffers that lie at multiples of a large power of two
- * from one another put equal offsets of all ranks on the same HBM channel and
- * bank; a few tens of KiB of extra distance avoids that.)
+ * (Performance only: buffers that start on 1 KiB boundaries, as allocators
+ * hand them out, are fastest: a wave moves 1 KiB per access, and buffers that
+ * start 16 bytes off such a boundary cost a fifth of the throughput, 256 bytes
+ * off a twentieth.  Some distances between the buffers put equal offsets of
+ * all ranks on the same HBM channel; the kernel spreads its accesses so that
+ * this costs at most a sixth, on few distances.)
  * The call enqueues one kernel on `stream` (a hipStream_t passed as void*;
  * null = the default stream) and returns without waiting; when the stream
  * reaches the end of that kernel every bufs[i] holds the result:

@@ -141,9 +141,11 @@ blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipSt
 // Tile size, kernel flavour and ticket count of a schedule on this device.
 //
 // The tile is large enough that a ticket moves about kTicketBytes.  A payload
-// too small to give a streaming grid a few dozen such tickets per CU is
-// latency-bound instead ("wide"): then all the waves that fit are used and the
-// tile shrinks until about every other wave has one.
+// too small to give a streaming grid 16 such tickets per CU is latency-bound
+// instead ("wide"): then all the waves that fit are used and the tile shrinks
+// until about every other wave has one.  (Measured on 8 ranks, 4 trees: at 11
+// tickets per CU the wide launch takes 52 us and the streaming one 72, at 16
+// they tie at 79, at 18 it is 157 against 130, at 23 161 against 143.)
 blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
     LaunchPlan& pl = h->plan;
     if (pl.made) return BLINK_OK;
@@ -163,7 +165,7 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
     unsigned tile = kMinTile;
     while (tile < kMaxTile && 2ull * tile * tile * bytes_per_elem * bytes_per_elem < ticket_bytes * ticket_bytes)
         tile *= 2;
-    pl.wide = work / tile < 24ull * h->n_cu;
+    pl.wide = work / tile < 16ull * h->n_cu;
 
     const uint64_t write_bytes = s.traffic_bytes - s.read_bytes;
     pl.read_heavy = s.read_bytes >= 2 * write_bytes;
