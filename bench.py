@@ -65,6 +65,10 @@ def parse():
     ap.add_argument("--config", choices=sorted(CONFIGS), default="headline",
                     help="benchmark configuration (default: the headline workload)")
     ap.add_argument("--fusion", choices=["edge", "node", "tree"], default="tree")
+    ap.add_argument("--sweep", choices=["alternate", "forward"], default="alternate",
+                    help="alternate (the library's default): every other call goes through the payload backwards, "
+                         "starting on what the call before it left in the 256 MiB memory-side cache; "
+                         "forward: every call goes forwards and streams past that cache")
     ap.add_argument("--collective", choices=["allreduce", "broadcast"], default=None,
                     help="override the configuration's collective")
     ap.add_argument("--chunk-bytes", type=int, default=0, help="override the configuration's chunk size")
@@ -257,6 +261,8 @@ def main():
     if args.tile_elems or args.wg_per_cu:
         for s in scheds:
             s.set_launch(args.wg_per_cu, args.tile_elems)
+    for s in scheds:
+        s.set_sweep(args.sweep == "alternate")
 
     # Inputs from the shared seeded recipe, resident in HBM before anything is
     # timed.  Rank buffers whose distances are large powers of two put equal
@@ -402,6 +408,7 @@ def main():
                    "stages": sum(s.num_stages for s in scheds),
                    "steps_in_schedule": sum(s.num_steps for s in scheds),
                    "restores_in_timed_region": restores, "setup_calls_per_schedule": SETUP_CALLS,
+                   "sweep": args.sweep,
                    "kernel_serving": sorted({s.last_kernel for s in scheds}), "commit": git_head()},
         "roofline": roofline,
     }

@@ -263,7 +263,8 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
  * longest one).  Wavefronts take tickets in ascending order.  Where the order
  * is free (no stage waits for another) the tickets walk tile by tile across the
  * trees (section 4.2.2: trees sharing the machine take turns) unless a stage
- * reads more than 8 ranks.  *n_tickets receives the count; stage and tile (host,
+ * reads more than 8 ranks, and calls may go through this list in alternating
+ * directions (blink_schedule_set_sweep).  *n_tickets receives the count; stage and tile (host,
  * caller-allocated, that many entries) may both be null to ask for the count. */
 blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t tile_elems, uint64_t* n_tickets,
                                           int32_t* stage, int32_t* tile);
@@ -356,6 +357,16 @@ blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int
  * before the first call). */
 blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel);
 int blink_schedule_last_kernel(const blink_schedule_t* s);
+/* The order in which a call works through the payload is free where no stage
+ * waits for another (whole-tree fusion).  alternate = 1 (the default): the
+ * second, fourth, ... call on such a schedule goes through the tiles backwards
+ * and results are written with a policy that lets them stay in the GPU's
+ * 256 MiB memory-side cache, so a call on the buffers of the call before it
+ * (training iterations without much else in between, benchmark loops) starts
+ * on data that is still there.  alternate = 0: every call goes forwards and
+ * streams its stores past the cache.  Same bits either way; schedules with
+ * dependencies and blink_allreduce_noalloc always go forwards. */
+blink_status_t blink_schedule_set_sweep(blink_schedule_t* s, int alternate);
 
 /* What became of the calls made on a schedule so far.  In the per-edge and
  * per-node programs a stage waits, chunk by chunk, for the stages it depends on

@@ -53,7 +53,7 @@ EXPORTS = [
     "blink_miad_free", "blink_make_schedule_servers", "blink_hybrid_split",
     "blink_schedule_get_stages", "blink_schedule_status", "blink_schedule_reset",
     "blink_schedule_set_wait_limit", "blink_schedule_test_skip_call", "blink_allreduce_noalloc",
-    "blink_schedule_set_kernel", "blink_schedule_last_kernel", "blink_schedule_get_tickets", "blink_schedule_batch",
+    "blink_schedule_set_kernel", "blink_schedule_last_kernel", "blink_schedule_set_sweep", "blink_schedule_get_tickets", "blink_schedule_batch",
 ]
 
 
@@ -142,6 +142,7 @@ def lib() -> C.CDLL:
     L.blink_schedule_set_kernel.argtypes = [vp, C.c_int]
     L.blink_schedule_get_tickets.argtypes = [vp, C.c_uint32, C.POINTER(C.c_uint64), vp, vp]
     L.blink_schedule_last_kernel.argtypes = [vp]
+    L.blink_schedule_set_sweep.argtypes = [vp, C.c_int]
     L.blink_miad_create.argtypes = [C.c_size_t, C.c_double, C.c_size_t, C.c_size_t, C.c_size_t,
                                     C.c_double, C.POINTER(vp)]
     L.blink_miad_chunk.argtypes = [vp]
@@ -299,6 +300,9 @@ class Schedule:
 
     def set_kernel(self, kernel: int) -> None:
         _check(lib().blink_schedule_set_kernel(self._h, kernel), "blink_schedule_set_kernel")
+
+    def set_sweep(self, alternate: bool) -> None:
+        _check(lib().blink_schedule_set_sweep(self._h, 1 if alternate else 0), "blink_schedule_set_sweep")
 
     @property
     def last_kernel(self) -> int:

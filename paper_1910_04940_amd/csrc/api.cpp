@@ -319,6 +319,18 @@ blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel) {
 
 int blink_schedule_last_kernel(const blink_schedule_t* s) { return s ? s->last_kernel : 0; }
 
+blink_status_t blink_schedule_set_sweep(blink_schedule_t* s, int alternate) {
+    if (!s || (alternate != 0 && alternate != 1)) return BLINK_EINVAL;
+    if (s->sweep_alternates != (alternate == 1)) {
+        s->sweep_alternates = alternate == 1;
+        // the cache policy, hence the kernel instantiation, follows the mode;
+        // tile size and counters do not
+        s->plan.made = false;
+        for (auto& per_dtype : s->occupancy) per_dtype[0] = per_dtype[1] = 0;
+    }
+    return BLINK_OK;
+}
+
 const char* blink_strerror(blink_status_t st) {
     switch (st) {
         case BLINK_OK: return "ok";

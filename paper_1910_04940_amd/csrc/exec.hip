@@ -172,13 +172,17 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
     const bool write_heavy = write_bytes >= 2 * s.read_bytes;
     // Rank buffers that together fit the memory-side cache (256 MiB) are written
     // without the streaming hint: whoever reads the result next (here: the next
-    // call) finds it there (8 x 16 MiB: 62 -> 45 us per call; no change from
-    // 8 x 64 MiB on, and a loss at 8 x 256 MiB).  That is the read-heavy policy.
+    // call) finds it there (8 x 16 MiB: 62 -> 45 us per call).  That is the
+    // read-heavy policy.  Larger buffers get it too where calls alternate their
+    // direction: a call then starts on the last 256 MiB that the call before it
+    // wrote (standalone probe, same kernel structure, repeated in place: 3 ranks x
+    // 128 MiB 0.75 -> 0.83 of the HBM peak, 8 x 64 MiB 0.72 -> 0.81, 8 x 256 MiB
+    // 0.774 -> 0.787; without the alternation the two policies tie).
     const bool fits_cache = static_cast<uint64_t>(s.k) * s.n * 4 <= kMemorySideCacheBytes;
     pl.flavour = s.has_deps   ? kHandOver
                  : write_heavy ? kWriteHeavy
-                 : (pl.read_heavy || fits_cache) ? kReadHeavy
-                                                 : kBalanced;
+                 : (pl.read_heavy || fits_cache || h->sweep_alternates) ? kReadHeavy
+                                                                        : kBalanced;
     if (pl.wide) {
         int& occ = h->occupancy[dtype == BLINK_FP32][0];
         if (occ == 0) {
@@ -421,6 +425,9 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
     p.group = ticket_group(s);
+    // Calls on a schedule without dependencies sweep the payload in alternating
+    // directions (the second, fourth, ... call backwards), unless switched off.
+    p.reverse = !s.has_deps && !static_block && h->sweep_alternates && (p.epoch & 1) == 0;
     // Waiting waves look at their dependency every ~0.2 us in small schedules,
     // where a hand-over is most of the time (16 one-hop trees, 256 elements,
     // per-edge: 47 -> 36 us), and back off to ~0.8 us in large ones.

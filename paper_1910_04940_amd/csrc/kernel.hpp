@@ -112,6 +112,7 @@ struct KParams {
     unsigned redop;       // blink_redop_t
     unsigned group;  // consecutive instances whose tiles are handed out in turn (1 = instance by instance)
     unsigned max_naps;  // longest pause between two looks at a dependency, in units of ~0.2 us
+    unsigned reverse;   // tickets walk the tiles from the last to the first (schedules without dependencies only)
 };
 
 // Address spaces: the kernel arguments and the schedule tables are never
@@ -497,6 +498,10 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
             }
         }
         if (t >= n_items) break;
+        // Every other call on a schedule whose stages do not wait for one
+        // another walks the tiles backwards: it starts where the call before it
+        // ended, on what that call left in the memory-side cache.
+        if (p->reverse) t = n_items - 1 - t;
         // ticket -> (instance, tile).  Within a group of `group` consecutive
         // instances (the trees' turns at one chunk position) tickets walk tile
         // by tile across the instances, so neighbouring waves work on all trees

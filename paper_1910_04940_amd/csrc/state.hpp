@@ -53,6 +53,7 @@ struct blink_schedule {
     int last_static_device = -1;  // device whose static block the latest call used; -1 = it used d_block
     // Which of the two kernels serves a schedule that both can run (see execute):
     int kernel_choice = 0;        // the caller's wish: 0 = pick the faster, 1 = blink_consume, 2 = blink_stream
+    bool sweep_alternates = true; // calls on a schedule without dependencies walk the tiles in alternating directions
     int picked = 0;               // the pick once made (1 or 2); 0 = not yet
     int trial_calls = 0;          // timed calls launched so far (they alternate between the two kernels)
     void* trial_event[16] = {};   // hipEvent_t pairs around the timed calls

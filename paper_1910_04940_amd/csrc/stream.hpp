@@ -103,6 +103,7 @@ struct Resolver {
     ConstInst inst;
     TicketSource tickets;
     unsigned tiles_per_chunk, tile_shift, group, n_inst;
+    bool reverse;
 
     // ticket -> (instance, tile), as in blink_consume: tile by tile across the
     // trees' turns at one chunk position (section 4.2.2).  Tickets of instances
@@ -112,7 +113,8 @@ struct Resolver {
         out.tlen = 0;
         while (t < tickets.n_items) {
             unsigned ii, tile;
-            ticket_to_tile(t, group, tiles_per_chunk, n_inst, &ii, &tile);
+            // every other call walks the tiles backwards (see blink_consume)
+            ticket_to_tile(reverse ? tickets.n_items - 1 - t : t, group, tiles_per_chunk, n_inst, &ii, &tile);
             ConstInst in = inst + ii;
             const unsigned long long off = in->off, end = off + in->len;
             const unsigned long long block = (off >> tile_shift) + tile;
@@ -320,6 +322,7 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
     res.tiles_per_chunk = p->tiles_per_chunk;
     res.tile_shift = p->tile_shift;
     res.group = p->group;
+    res.reverse = p->reverse != 0;
     res.n_inst = static_cast<unsigned>(p->n_items / p->tiles_per_chunk);
     res.tickets.counter = p->ticket;
     res.tickets.base = p->ticket_base[0];

@@ -139,3 +139,36 @@ def test_automatic_choice_times_both_and_settles():
         bl.blink_allreduce(bufs, m, bl.BLINK_INT32, small, stream)
         assert small.last_kernel == 1
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_alternating_sweep_gives_the_same_bits_as_forward_calls(kernel):
+    """Every other call on a dependency-free schedule goes through the tiles
+    backwards (the default); with that switched off all go forwards.  Four calls
+    in a row, ragged size: the same bits after every call, and the oracle's."""
+    dev, stream = _dev()
+    top = si.hybrid_cube_mesh()
+    n, chunk, k = (1 << 24) + 1_027, 250_001, 8
+    trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
+    roots, parents, w = trees.as_lists()
+    x = [si.hash_payload(29, r, 0, n, "fp32") for r in range(k)]
+    results = {}
+    for alternate in (True, False):
+        sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+        sched.set_kernel(kernel)
+        sched.set_sweep(alternate)
+        bufs = [torch.from_numpy(a).to(dev) for a in x]
+        after = []
+        for _ in range(4):
+            bl.blink_allreduce(bufs, n, bl.BLINK_FP32, sched, stream)
+            torch.cuda.synchronize()
+            assert sched.last_kernel == kernel
+            after.append([b.cpu().numpy().view(np.uint32).copy() for b in bufs])
+        results[alternate] = after
+    want = [a.copy() for a in x]
+    for call in range(4):
+        summed = ox.tree_order_allreduce(want, roots, parents, w)
+        want = [summed.copy() for _ in range(k)]
+        for r in range(k):
+            assert np.array_equal(results[True][call][r], results[False][call][r]), (call, r)
+            assert np.array_equal(results[True][call][r], summed.view(np.uint32)), (call, r)

@@ -351,3 +351,17 @@ def test_gather_needs_a_multiple_of_k():
     with pytest.raises(bl.BlinkError) as e:
         bl.blink_make_schedule(trees, bl.BLINK_OP_ALLGATHER, 4 * 100 + 2, 64)
     assert e.value.status == bl.BLINK_EINVAL
+
+
+def test_sweep_switch_takes_zero_or_one():
+    """blink_schedule_set_sweep: host-side state only, no GPU needed."""
+    from paper_1910_04940_amd import binding
+    top = si.hybrid_cube_mesh()
+    trees = bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 1 << 16, 1 << 12, bl.BLINK_FUSE_TREE)
+    sched.set_sweep(False)
+    sched.set_sweep(True)
+    lib = binding.lib()
+    assert lib.blink_schedule_set_sweep(sched._h, 2) == bl.BLINK_EINVAL
+    assert lib.blink_schedule_set_sweep(sched._h, -1) == bl.BLINK_EINVAL
+    assert lib.blink_schedule_set_sweep(None, 1) == bl.BLINK_EINVAL
