@@ -263,8 +263,9 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
  * longest one).  Wavefronts take tickets in ascending order.  Where the order
  * is free (no stage waits for another) the tickets walk tile by tile across the
  * trees (section 4.2.2: trees sharing the machine take turns) unless a stage
- * reads more than 8 ranks, and calls may go through this list in alternating
- * directions (blink_schedule_set_sweep).  *n_tickets receives the count; stage and tile (host,
+ * reads more than 8 ranks, calls may go through this list in alternating
+ * directions (blink_schedule_set_sweep), and for rank buffers that all start the
+ * same distance past a 1 KiB boundary the blocks are counted from that boundary.  *n_tickets receives the count; stage and tile (host,
  * caller-allocated, that many entries) may both be null to ask for the count. */
 blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t tile_elems, uint64_t* n_tickets,
                                           int32_t* stage, int32_t* tile);
@@ -279,12 +280,14 @@ void blink_schedule_free(blink_schedule_t* s);
 
 /* bufs: HOST array of k DEVICE pointers; each buffer holds at least n_elems
  * 4-byte elements, is 16-byte aligned and overlaps no other.  In place.
- * (Performance only: buffers that start on 1 KiB boundaries, as allocators
- * hand them out, are fastest: a wave moves 1 KiB per access, and buffers that
- * start 16 bytes off such a boundary cost a fifth of the throughput, 256 bytes
- * off a twentieth.  Some distances between the buffers put equal offsets of
- * all ranks on the same HBM channel; the kernel spreads its accesses so that
- * this costs at most a sixth, on few distances.)
+ * (Performance only: a wave moves 1 KiB per access and wants it to start on a
+ * 1 KiB boundary in memory.  Buffers that all start the same distance past such
+ * a boundary (allocations, equal offsets into larger buffers) get that at any
+ * distance; buffers that differ in it lose up to a quarter of the throughput
+ * when the differences are odd multiples of 16 bytes, a twentieth at multiples
+ * of 128.  Some distances between the buffers put equal offsets of all ranks on
+ * the same HBM channel; the kernel spreads its accesses so that this costs at
+ * most a sixth, on few distances.)
  * The call enqueues one kernel on `stream` (a hipStream_t passed as void*;
  * null = the default stream) and returns without waiting; when the stream
  * reaches the end of that kernel every bufs[i] holds the result:

@@ -138,6 +138,20 @@ blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipSt
     return BLINK_OK;
 }
 
+// Tickets of a schedule whose tile grid is moved down by grid_shift elements:
+// as many per stage instance as the instance with the most tiles has.
+void count_tickets(blink_schedule* h, uint32_t grid_shift) {
+    LaunchPlan& pl = h->plan;
+    const uint64_t tile = pl.tile_elems;
+    uint64_t tiles_per_chunk = 1;
+    for (const StageInst& in : h->s.inst)
+        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk, ((in.off + grid_shift + in.len + tile - 1) >> pl.tile_shift) -
+                                                                  ((in.off + grid_shift) >> pl.tile_shift));
+    pl.tiles_per_chunk = static_cast<uint32_t>(tiles_per_chunk);
+    pl.n_items = static_cast<uint64_t>(h->s.inst.size()) * tiles_per_chunk;
+    pl.grid_shift = grid_shift;
+}
+
 // Tile size, kernel flavour and ticket count of a schedule on this device.
 //
 // The tile is large enough that a ticket moves about kTicketBytes.  A payload
@@ -211,13 +225,8 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
     pl.tile_elems = tile;
     pl.tile_shift = 0;
     while ((1u << pl.tile_shift) < tile) ++pl.tile_shift;
-    uint64_t tiles_per_chunk = 1;
-    for (const StageInst& in : s.inst)
-        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk,
-                                             ((in.off + in.len + tile - 1) >> pl.tile_shift) - (in.off >> pl.tile_shift));
-    pl.tiles_per_chunk = static_cast<uint32_t>(tiles_per_chunk);
-    pl.n_items = static_cast<uint64_t>(s.inst.size()) * tiles_per_chunk;
     pl.made = true;
+    count_tickets(h, 0);
     return BLINK_OK;
 }
 
@@ -370,6 +379,21 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         h->last_static_device = -1;
     }
     if (blink_status_t st = make_plan(h, dtype)) return st;
+    // Rank buffers that all start the same distance past a 1 KiB boundary (views
+    // into larger buffers, allocations at 512-byte granularity): the tile grid
+    // is moved down by that distance, so that tiles, and with them the 1 KiB
+    // accesses of a wave, start on such boundaries in memory.  Only where no
+    // stage waits for another: there a tile is nothing but a range of elements;
+    // with dependencies finished tiles are counted, per call number, and the
+    // count of an instance must not change from call to call.
+    uint32_t grid_shift = 0;
+    if (!s.has_deps) {
+        const uintptr_t past = reinterpret_cast<uintptr_t>(bufs[0]) & 1023u;
+        bool common = true;
+        for (int i = 1; i < k; ++i) common = common && (reinterpret_cast<uintptr_t>(bufs[i]) & 1023u) == past;
+        if (common) grid_shift = static_cast<uint32_t>(past / 4);
+    }
+    if (grid_shift != h->plan.grid_shift) count_tickets(h, grid_shift);
     const LaunchPlan& pl = h->plan;
 
     int timed = -1;
@@ -425,6 +449,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
     p.group = ticket_group(s);
+    p.grid_shift = pl.grid_shift;
     // Calls on a schedule without dependencies sweep the payload in alternating
     // directions (the second, fourth, ... call backwards), unless switched off.
     p.reverse = !s.has_deps && !static_block && h->sweep_alternates && (p.epoch & 1) == 0;

@@ -19,6 +19,7 @@ struct LaunchPlan {
     unsigned tile_elems = 0;       // elements per tile
     unsigned tile_shift = 0;       // log2 of it
     uint32_t tiles_per_chunk = 1;  // most tiles any stage instance has
+    uint32_t grid_shift = 0;       // elements the tile grid is moved down by (see execute)
     uint64_t n_items = 0;          // tickets per call
     bool read_heavy = false;
     bool direct = false;           // the schedule CAN run on the streaming kernel (stream.hpp)

@@ -103,6 +103,7 @@ struct Resolver {
     ConstInst inst;
     TicketSource tickets;
     unsigned tiles_per_chunk, tile_shift, group, n_inst;
+    unsigned long long grid_shift;
     bool reverse;
 
     // ticket -> (instance, tile), as in blink_consume: tile by tile across the
@@ -116,10 +117,12 @@ struct Resolver {
             // every other call walks the tiles backwards (see blink_consume)
             ticket_to_tile(reverse ? tickets.n_items - 1 - t : t, group, tiles_per_chunk, n_inst, &ii, &tile);
             ConstInst in = inst + ii;
+            // the tile grid, moved down by grid_shift elements (see blink_consume)
             const unsigned long long off = in->off, end = off + in->len;
-            const unsigned long long block = (off >> tile_shift) + tile;
-            const unsigned long long lo_e = max(off, block << tile_shift);
-            const unsigned long long hi_e = min(end, (block + 1) << tile_shift);
+            const unsigned long long block = ((off + grid_shift) >> tile_shift) + tile;
+            const unsigned long long block_lo = block << tile_shift;
+            const unsigned long long lo_e = block_lo > grid_shift ? max(off, block_lo - grid_shift) : off;
+            const unsigned long long hi_e = min(end, block_lo + (1ull << tile_shift) - grid_shift);
             if (lo_e < hi_e) {
                 out.first = lo_e;
                 out.tlen = static_cast<unsigned>(hi_e - lo_e);
@@ -323,6 +326,7 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
     res.tile_shift = p->tile_shift;
     res.group = p->group;
     res.reverse = p->reverse != 0;
+    res.grid_shift = p->grid_shift;
     res.n_inst = static_cast<unsigned>(p->n_items / p->tiles_per_chunk);
     res.tickets.counter = p->ticket;
     res.tickets.base = p->ticket_base[0];

@@ -172,3 +172,43 @@ def test_alternating_sweep_gives_the_same_bits_as_forward_calls(kernel):
         for r in range(k):
             assert np.array_equal(results[True][call][r], results[False][call][r]), (call, r)
             assert np.array_equal(results[True][call][r], summed.view(np.uint32)), (call, r)
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("past", [(16,) * 8, (512,) * 8, (1008,) * 8, (0, 16, 32, 48, 512, 528, 1008, 64)])
+def test_rank_buffers_that_do_not_start_on_1k_boundaries(kernel, past):
+    """Rank buffers that are views into larger ones.  Where all of them start
+    the same distance past a 1 KiB boundary the library moves its tile grid by
+    that distance; where they differ it does not.  Same bits as the oracle in
+    both cases, over three calls (the second goes through the tiles backwards)."""
+    dev, stream = _dev()
+    top = si.hybrid_cube_mesh()
+    n, chunk, k = (1 << 24) + 2_051, 1 << 18, 8
+    trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
+    roots, parents, w = trees.as_lists()
+    x = [si.hash_payload(31, r, 0, n, "int32") for r in range(k)]
+    stride = n + 4096
+    slab = torch.zeros(k * stride + 1024, dtype=torch.int32, device=dev)
+    assert slab.data_ptr() % 1024 == 0
+    bufs = []
+    for r in range(k):
+        first = r * stride + (-(r * stride) % 256) + past[r] // 4      # elements; 256 elements = 1 KiB
+        bufs.append(slab[first:first + n])
+        assert bufs[r].data_ptr() % 1024 == past[r]
+        bufs[r].copy_(torch.from_numpy(x[r]))
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+    sched.set_kernel(kernel)
+    want = ox.allreduce_int32_definition(x).view(np.uint32).astype(np.uint64)
+    for call in range(3):
+        bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream)
+        torch.cuda.synchronize()
+        assert sched.last_kernel == kernel
+        expect = ((want * np.uint64(pow(8, call, 1 << 32))) & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+        for r in range(k):
+            assert np.array_equal(bufs[r].cpu().numpy().view(np.uint32), expect), (call, r)
+    # nothing outside the views was written
+    outside = slab.clone()
+    for b in bufs:
+        b.zero_()
+    assert int(torch.count_nonzero(slab)) == 0, "bytes outside the rank buffers were written"
+    del outside
