@@ -65,6 +65,7 @@ def parse():
     ap.add_argument("--config", choices=sorted(CONFIGS), default="headline",
                     help="benchmark configuration (default: the headline workload)")
     ap.add_argument("--fusion", choices=["edge", "node", "tree"], default="tree")
+    ap.add_argument("--progress", action="store_true", help="say on stderr what is being done (for slow, profiled runs)")
     ap.add_argument("--sweep", choices=["alternate", "forward"], default="alternate",
                     help="alternate (the library's default): every other call goes through the payload backwards, "
                          "starting on what the call before it left in the 256 MiB memory-side cache; "
@@ -221,6 +222,10 @@ def git_head():
 
 def main():
     args = parse()
+
+    def say(what):
+        if args.progress:
+            print(f"bench.py: {what}", file=sys.stderr, flush=True)
     if args.calibrate_copy:
         calibrate_copy(args.steps)
         return
@@ -278,7 +283,10 @@ def main():
     offset = 0
     for m, sched in zip(sizes, scheds):
         if dist == "hash":
-            pristine = [si.hash_payload_torch(0, r, m, args.dtype, dev) for r in range(k)]
+            pristine = []
+            for r in range(k):
+                pristine.append(si.hash_payload_torch(0, r, m, args.dtype, dev))
+                say(f"payload of rank {r} generated")
         else:
             pristine = [torch.from_numpy(host_payload(si, 0, r, m, dist, args.dtype, scale, start=offset)).to(dev)
                         for r in range(k)]
@@ -314,10 +322,12 @@ def main():
     # library spends a schedule's first nine calls choosing between its two
     # kernels (eight timed calls, then one that waits for them).
     SETUP_CALLS = 9
+    say("inputs are on the device")
     restore()
     for _ in range(SETUP_CALLS):
         step()
     torch.cuda.synchronize()
+    say("set-up calls done")
     since_restore = 0
     restore()
     for _ in range(args.warmup):
@@ -330,6 +340,7 @@ def main():
     since_restore = 0
     restores = 0
     torch.cuda.synchronize()
+    say("warm-up done")
 
     # Kernel time with HIP events on the launch stream.  Launches follow one another
     # without a gap while the stream has work queued, so the average duration of a
@@ -370,6 +381,7 @@ def main():
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
     prof_name = (f"blink_consume_{collective}_cube8_{n * 4 >> 20}MiB_{args.fusion}.txt" if args.config == "headline"
                  else f"config{args.config}_{collective}_{args.fusion}.txt")
+    say("timed steps done")
     traffic, traffic_digest = traffic_from_profiles(prof_name)
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS,
