@@ -408,15 +408,16 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         }
     }
     // Waves per CU.  blink_stream: 2, each with 64 KiB of loads in flight (all
-    // that fit).  blink_consume: 2 waves with 32 KiB each, 3 where stages wait for
-    // one another, where reads dominate, or where a stage reads more than 8 ranks
-    // (only 2 columns per rank fit then); 1 where writes dominate (Broadcast,
+    // that fit).  blink_consume: 2 waves with 32 KiB each; 3 where reads dominate
+    // or where a stage reads more than 8 ranks (only 2 columns per rank fit
+    // then); 4 where stages wait for one another (some waves always wait; 8 x
+    // 256 MiB per node 1.088 -> 1.023 ms, per edge 1.242 -> 1.230); 1 where writes dominate (Broadcast,
     // AllGather: a wave's sub-tile is then one read and seven writes of 16 KiB
     // each, and a second wave per CU only adds to the queue of stores; 8 ranks,
     // Broadcast: 8 x 64 MiB 83 -> 71 us, 8 x 256 MiB 300 -> 271 us; AllGather
     // 81 -> 73 us and 312 -> 302 us).
     const bool write_heavy = pl.flavour == kWriteHeavy;
-    int per_cu = std::min(occ, direct ? 2 : write_heavy ? 1 : (pl.read_heavy || s.has_deps || s.max_slots > 8 ? 3 : 2));
+    int per_cu = std::min(occ, direct ? 2 : write_heavy ? 1 : s.has_deps ? 4 : (pl.read_heavy || s.max_slots > 8 ? 3 : 2));
     if (h->wg_per_cu > 0) per_cu = std::min(occ, h->wg_per_cu);
     if (pl.wide && h->wg_per_cu == 0) per_cu = occ;
     unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
