@@ -443,12 +443,16 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     for (unsigned q = 0; q < n_queues; ++q) p.ticket_base[q] = static_block ? 0 : h->ticket_base[q];
     p.n_items = n_items;
     // A dependency-free schedule with at most four tickets per wave is dealt out
-    // statically, without the counter (see the kernel).  Larger ones draw every
-    // ticket: waves then advance as one compact front through memory, which
-    // DRAM likes better (measured: 0.71 ms against 0.79 ms on the 256 MiB case).
-    // With dependencies every ticket must come from the counter: only then is
-    // a ticket's holder known to be running.
-    const unsigned long long static_items = (!s.has_deps && n_items / grid <= 4) ? n_items : 0;
+    // statically, without the counter (see the kernel).  Larger ones draw their
+    // tickets: waves then advance as one compact front through memory, which
+    // DRAM likes better (measured: 0.71 ms against 0.79 ms on the 256 MiB case);
+    // but every wave's first ticket is its own number: drawn, the first tickets
+    // of 512 waves queue at the counter for up to 8 us (4.4 us on average, seen
+    // with a clock in every wave), which is 2 % of a 200 us call.  blink_stream
+    // knows all or nothing.  With dependencies every ticket must come from the
+    // counter: only then is a ticket's holder known to be running.
+    const unsigned long long static_items =
+        s.has_deps ? 0 : (n_items / grid <= 4 ? n_items : (direct ? 0 : grid));
     p.static_items = static_items;
     p.epoch = static_block ? 1 : h->epoch + 1;
     p.tiles_per_chunk = pl.tiles_per_chunk;
