@@ -29,9 +29,9 @@
  *     in time on the same schedule race (stages of one may then wait for
  *     progress the other consumed; such a wait is bounded, see
  *     blink_schedule_status).  Every launch carries the number of
- *     the call on its schedule, so a call must not be recorded into a HIP graph
- *     (a replay would repeat a number); the first call on a schedule also
- *     allocates, which a capturing stream forbids anyway.
+ *     the call on its schedule, so a call cannot be recorded into a HIP graph
+ *     (a replay would repeat a number): on a capturing stream every collective
+ *     but blink_allreduce_noalloc returns BLINK_EINVAL and records nothing.
  *   - At most BLINK_MAX_RANKS ranks.
  */
 #ifndef BLINK_H
@@ -335,8 +335,13 @@ blink_status_t blink_gather(void* const* bufs, int k, size_t n_elems, blink_dtyp
  * they use: calls that overlap in time on one GPU race.  Each call clears the
  * counters it needs on `stream` before its kernel.  When the block last held
  * another schedule's tables the call first waits for `stream` and copies its own
- * in synchronously (so under graph capture, make one call on the schedule
- * beforehand).  blink_schedule_status reports on
+ * in synchronously; a capturing stream can record neither, so there the call
+ * returns BLINK_EINVAL and records nothing: make one call on the schedule before
+ * the capture.  A recorded call starts from cleared counters like any other and
+ * may be replayed any number of times, as long as the block still holds its
+ * schedule's tables at every replay (no call of this function on another
+ * schedule in between: the replay would run on the other's tables).
+ * blink_schedule_status reports on
  * the block the latest call of the schedule used.  blink_allreduce and the other
  * entry points are unaffected and may be mixed with this one on one schedule. */
 blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems, blink_dtype_t dtype,

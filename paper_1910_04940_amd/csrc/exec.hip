@@ -127,6 +127,15 @@ blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipSt
         sb.ptr = ptr;
     }
     if (sb.owner != h->id) {
+        // waiting and copying are not things a capturing stream can record
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+            (void)hipGetLastError();
+        } else if (capture != hipStreamCaptureStatusNone) {
+            std::fprintf(stderr, "blink: the stream is capturing and the static block holds another schedule's tables; "
+                                 "call blink_allreduce_noalloc on this schedule once before the capture\n");
+            return BLINK_EINVAL;
+        }
         sb.owner = 0;
         BLINK_HIP(hipStreamSynchronize(stream));
         BLINK_HIP(hipMemcpy(sb.ptr + l.tmpl, h->s.tmpl.data(), h->s.tmpl.size() * sizeof(StageTmpl), hipMemcpyHostToDevice));
@@ -374,6 +383,17 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     if (static_block) {
         if (blink_status_t st = claim_static_block(h, l, static_cast<hipStream_t>(stream), &block)) return st;
     } else {
+        // A launch carries the call's number on its schedule and the place its
+        // ticket counters have reached; replayed from a HIP graph it would carry
+        // them again and find the counters elsewhere: waves would draw nothing
+        // and stages would not wait.  Say so instead of recording such a launch.
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) != hipSuccess) {
+            (void)hipGetLastError();  // not this call's business: the launch will report a bad stream
+        } else if (capture != hipStreamCaptureStatusNone) {
+            std::fprintf(stderr, "blink: the stream is capturing; only blink_allreduce_noalloc can be recorded into a HIP graph\n");
+            return BLINK_EINVAL;
+        }
         if (blink_status_t st = upload(h)) return st;
         block = static_cast<char*>(h->d_block);
         h->last_static_device = -1;
