@@ -68,3 +68,54 @@ def test_many_unevenly_weighted_trees_from_real_valued_capacities(dev, seed, fus
     torch.cuda.synchronize()
     for b in bufs:
         assert b.cpu().numpy().tobytes() == want.tobytes()
+
+
+def streaming_case(seed):
+    """Random trees on a payload large enough for the streaming launch (about
+    1 GiB of traffic), ragged, in views that start a random distance past a
+    1 KiB boundary: the same distance for all ranks, or one of its own each."""
+    k, roots, parents, w, _, _ = random_case(1000 + seed, same_root=False)
+    rng = np.random.default_rng([79, seed])
+    n = (1 << 27) // k + int(rng.integers(0, 5000))
+    chunk = int(rng.integers(50_000, 2_000_000))
+    if seed % 3 == 0:
+        past = [0] * k
+    elif seed % 3 == 1:
+        past = [16 * int(rng.integers(0, 64))] * k
+    else:
+        past = [16 * int(v) for v in rng.integers(0, 64, k)]
+    return k, roots, parents, w, n, chunk, past
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_trees_at_streaming_size_over_three_calls(dev, seed):
+    """Either kernel, three calls in place (the second goes through the tiles
+    backwards): after call c every rank holds the oracle's sum times k^(c-1),
+    modulo 2^32, and no byte outside the views has changed."""
+    k, roots, parents, w, n, chunk, past = streaming_case(seed)
+    kernel = 1 + seed % 2
+    trees = bl.blink_trees_from_arrays(k, roots, parents, w)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+    sched.set_kernel(kernel)
+    x = [si.payload(200 + seed, r, n, "int", "int32") for r in range(k)]
+    stride = n + 4096
+    slab = torch.zeros(k * stride + 1024, dtype=torch.int32, device=dev)
+    assert slab.data_ptr() % 1024 == 0
+    bufs = []
+    for r in range(k):
+        first = r * stride + (-(r * stride) % 256) + past[r] // 4
+        bufs.append(slab[first:first + n])
+        assert bufs[r].data_ptr() % 1024 == past[r]
+        bufs[r].copy_(torch.from_numpy(x[r]))
+    print(f"seed {seed}: k={k} T={len(roots)} n={n} chunk={chunk} past={past} kernel={kernel}", flush=True)
+    want = ox.allreduce_int32_definition(x).view(np.uint32).astype(np.uint64)
+    for call in range(3):
+        bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream())
+        torch.cuda.synchronize()
+        expect = ((want * np.uint64(pow(k, call, 1 << 32))) & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+        for r in range(k):
+            assert np.array_equal(bufs[r].cpu().numpy().view(np.uint32), expect), (call, r, sched.last_kernel)
+    assert sched.status()[0] == bl.BLINK_OK
+    for b in bufs:
+        b.zero_()
+    assert int(torch.count_nonzero(slab)) == 0, "bytes outside the rank buffers were written"
