@@ -196,17 +196,15 @@ blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t ti
     const blink::Schedule& sc = s->s;
     unsigned shift = 0;
     while ((1u << shift) < tile_elems) ++shift;
-    uint64_t tiles_per_chunk = 1;
-    for (const blink::StageInst& in : sc.inst)
-        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk, ((in.off + in.len + tile_elems - 1) >> shift) - (in.off >> shift));
-    const uint64_t n = static_cast<uint64_t>(sc.inst.size()) * tiles_per_chunk;
+    uint32_t tiles_per_chunk = 1;
+    const uint64_t n = blink::ticket_count(sc, shift, 0, &tiles_per_chunk);
     *n_tickets = n;
     if (!stage && !tile) return BLINK_OK;
     if (!stage || !tile) return BLINK_EINVAL;
     const unsigned group = blink::ticket_group(sc);
     for (uint64_t t = 0; t < n; ++t) {
         unsigned ii, tt;
-        blink::ticket_to_tile(t, group, static_cast<unsigned>(tiles_per_chunk), static_cast<unsigned>(sc.inst.size()), &ii, &tt);
+        blink::ticket_to_tile(t, group, tiles_per_chunk, static_cast<unsigned>(sc.inst.size()), &ii, &tt);
         const blink::StageInst& in = sc.inst[ii];
         const uint64_t block = (in.off >> shift) + tt;
         const uint64_t lo = std::max<uint64_t>(in.off, block << shift), hi = std::min<uint64_t>(in.off + in.len, (block + 1) << shift);

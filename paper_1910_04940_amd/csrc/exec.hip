@@ -147,17 +147,10 @@ blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipSt
     return BLINK_OK;
 }
 
-// Tickets of a schedule whose tile grid is moved down by grid_shift elements:
-// as many per stage instance as the instance with the most tiles has.
+// Tickets of a schedule whose tile grid is moved down by grid_shift elements.
 void count_tickets(blink_schedule* h, uint32_t grid_shift) {
     LaunchPlan& pl = h->plan;
-    const uint64_t tile = pl.tile_elems;
-    uint64_t tiles_per_chunk = 1;
-    for (const StageInst& in : h->s.inst)
-        tiles_per_chunk = std::max<uint64_t>(tiles_per_chunk, ((in.off + grid_shift + in.len + tile - 1) >> pl.tile_shift) -
-                                                                  ((in.off + grid_shift) >> pl.tile_shift));
-    pl.tiles_per_chunk = static_cast<uint32_t>(tiles_per_chunk);
-    pl.n_items = static_cast<uint64_t>(h->s.inst.size()) * tiles_per_chunk;
+    pl.n_items = ticket_count(h->s, pl.tile_shift, grid_shift, &pl.tiles_per_chunk);
     pl.grid_shift = grid_shift;
 }
 
@@ -480,6 +473,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.redop = static_cast<unsigned>(redop);
     p.group = ticket_group(s);
     p.grid_shift = pl.grid_shift;
+    p.n_inst = static_cast<unsigned>(s.inst.size());
     // Calls on a schedule without dependencies sweep the payload in alternating
     // directions (the second, fourth, ... call backwards), unless switched off.
     p.reverse = !s.has_deps && !static_block && h->sweep_alternates && (p.epoch & 1) == 0;

@@ -114,6 +114,7 @@ struct KParams {
     unsigned max_naps;  // longest pause between two looks at a dependency, in units of ~0.2 us
     unsigned reverse;   // tickets walk the tiles from the last to the first (schedules without dependencies only)
     unsigned grid_shift;  // elements by which the tile grid is moved down (schedules without dependencies only)
+    unsigned n_inst;      // stage instances (n_items is less than n_inst * tiles_per_chunk where the last group has fewer tiles)
 };
 
 // Address spaces: the kernel arguments and the schedule tables are never
@@ -433,7 +434,7 @@ __global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
     const unsigned cols = min(tile_elems / kMinTile, static_cast<unsigned>(COLS));
     const unsigned group = p->group;
     const unsigned long long grid_shift = p->grid_shift;
-    const unsigned n_inst = static_cast<unsigned>(n_items / tiles_per_chunk);
+    const unsigned n_inst = p->n_inst;
 
     // Lane-dependent regions.  readfirstlane needs lane 0 present, so the
     // compiler must never get the chance to let some lanes run ahead of lane 0

@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kLanes) void blink_stream(const KParams) {
     res.group = p->group;
     res.reverse = p->reverse != 0;
     res.grid_shift = p->grid_shift;
-    res.n_inst = static_cast<unsigned>(p->n_items / p->tiles_per_chunk);
+    res.n_inst = p->n_inst;
     res.tickets.counter = p->ticket;
     res.tickets.base = p->ticket_base[0];
     res.tickets.n_items = p->n_items;

@@ -190,3 +190,36 @@ def test_tile_order_keeps_stages_together_where_that_is_the_rule():
     assert stage.tolist() == sorted(stage.tolist())
     with pytest.raises(bl.BlinkError):
         sched.tickets(1000)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_tickets_of_random_schedules_cover_every_tile_exactly_once(seed):
+    """Random trees, weights, sizes, chunk and tile sizes, every fusion level:
+    the tickets that stand for something are exactly the (stage, tile) pairs
+    that hold elements; and the last group of stages gets no more rounds of
+    tickets than its largest stage has tiles."""
+    from test_random_schedules import random_case
+    rng = np.random.default_rng([81, seed])
+    k, roots, parents, w, _, _ = random_case(3000 + seed, same_root=False)
+    n = int(rng.integers(1, 400_000))
+    chunk = int(rng.integers(1, 60_000))
+    tile = 1 << int(rng.integers(8, 13))
+    fusion = [bl.BLINK_FUSE_EDGE, bl.BLINK_FUSE_NODE, bl.BLINK_FUSE_TREE][seed % 3]
+    trees = bl.blink_trees_from_arrays(k, roots, parents, w)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, fusion)
+    stages = sched.stages()
+    stage, tl = sched.tickets(tile)
+    real = tl >= 0
+    want = set()
+    for i, s in enumerate(stages):
+        off, ln = int(s["off"]), int(s["len"])
+        for b in range(off // tile, (off + ln + tile - 1) // tile):
+            want.add((i, b - off // tile))
+    got = list(zip(stage[real].tolist(), tl[real].tolist()))
+    assert len(got) == len(set(got)) and set(got) == want
+    if len(stage):
+        # the last ticket's round is one some stage of its group needs
+        last_stage = int(stage[-1])
+        group = set(stage[np.flatnonzero(stage == last_stage)[0]:].tolist())
+        last_round = max(t for s_, t in want if s_ in group)
+        assert sum(1 for s_, t in zip(stage.tolist(), tl.tolist()) if s_ in group and t == last_round) >= 1
