@@ -265,8 +265,9 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
  * trees (section 4.2.2: trees sharing the machine take turns) unless a stage
  * reads more than 8 ranks, calls may go through this list in alternating
  * directions (blink_schedule_set_sweep), and for rank buffers that all start the
- * same distance past a 1 KiB boundary the blocks are counted from that boundary.  *n_tickets receives the count; stage and tile (host,
- * caller-allocated, that many entries) may both be null to ask for the count. */
+ * same distance past a 1 KiB boundary the blocks are counted from that boundary.
+ * *n_tickets receives the count; stage and tile (host, caller-allocated, that
+ * many entries) may both be null to ask for the count. */
 blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t tile_elems, uint64_t* n_tickets,
                                           int32_t* stage, int32_t* tile);
 /* out[T+1] (host): share boundaries b_0 = 0 .. b_T = n_elems. */
