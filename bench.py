@@ -319,9 +319,9 @@ def main():
             run(bufs, m, dtype, sched, stream.cuda_stream)
 
     # Set-up, outside warm-up and timing like the building of the schedules: the
-    # library spends a schedule's first nine calls choosing between its two
-    # kernels (eight timed calls, then one that waits for them).
-    SETUP_CALLS = 9
+    # library spends a schedule's first thirteen calls at most choosing among the
+    # ways it can serve it (twelve timed calls, then one that waits for them).
+    SETUP_CALLS = 13
     say("inputs are on the device")
     restore()
     for _ in range(SETUP_CALLS):

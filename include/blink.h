@@ -263,7 +263,9 @@ blink_status_t blink_schedule_get_stages(const blink_schedule_t* s, blink_stage_
  * longest one).  Wavefronts take tickets in ascending order.  Where the order
  * is free (no stage waits for another) the tickets walk tile by tile across the
  * trees (section 4.2.2: trees sharing the machine take turns) unless a stage
- * reads more than 8 ranks, calls may go through this list in alternating
+ * reads more than 8 ranks (the library may also serve a schedule chunk by chunk
+ * where it measured that to be faster, see blink_schedule_set_kernel), calls may
+ * go through this list in alternating
  * directions (blink_schedule_set_sweep), and for rank buffers that all start the
  * same distance past a 1 KiB boundary the blocks are counted from that boundary.
  * *n_tickets receives the count; stage and tile (host, caller-allocated, that
@@ -354,16 +356,20 @@ blink_status_t blink_allreduce_noalloc(void* const* bufs, int k, size_t n_elems,
  * device and restarts the schedule's progress counters.  Applies to later
  * calls on this schedule. */
 blink_status_t blink_schedule_set_launch(blink_schedule_t* s, int wg_per_cu, int tile_elems);
-/* Two kernels can run a sum over a schedule whose stages do not wait for one
- * another (whole-tree fusion) at streaming sizes; they give the same bits.
- * kernel: 0 = automatic (the first eight calls of at least 64 MiB of traffic
- * alternate between the two and are timed with events on the caller's stream;
- * the ninth call waits for them and the faster kernel serves from then on;
- * blink_allreduce_noalloc takes no part in the timing), 1 = the ticket-drawing kernel with
- * loads staged through registers, 2 = the streaming kernel with loads straight
- * into LDS.  Schedules only one of them can run are not affected.
- * blink_schedule_last_kernel: the kernel the latest call ran on (1 or 2; 0
- * before the first call). */
+/* A schedule whose stages do not wait for one another (whole-tree fusion) can
+ * be served in up to three ways at streaming sizes; they give the same bits.
+ * 1 = the ticket-drawing kernel with loads staged through registers; 2 = the
+ * streaming kernel with loads straight into LDS (sums only, stages within its
+ * limits); 3 = the ticket-drawing kernel with the trees taking turns chunk by
+ * chunk (section 4.2.2 at the paper's own granularity) instead of tile by tile
+ * (several trees only).  kernel: 0 = automatic: the first calls of at least
+ * 64 MiB of traffic go round the ways the schedule has, four times each (eight
+ * or twelve calls), timed with events on the caller's stream; the call after
+ * them waits for them, and the fastest way serves from then on
+ * (blink_allreduce_noalloc takes no part in the timing and uses way 1);
+ * 1, 2, 3 = that way, or way 1 where the schedule does not have it.
+ * blink_schedule_last_kernel: the way the latest call ran (0 before the first
+ * call). */
 blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel);
 int blink_schedule_last_kernel(const blink_schedule_t* s);
 /* The order in which a call works through the payload is free where no stage

@@ -197,11 +197,11 @@ blink_status_t blink_schedule_get_tickets(const blink_schedule_t* s, uint32_t ti
     unsigned shift = 0;
     while ((1u << shift) < tile_elems) ++shift;
     uint32_t tiles_per_chunk = 1;
-    const uint64_t n = blink::ticket_count(sc, shift, 0, &tiles_per_chunk);
+    const unsigned group = blink::ticket_group(sc);
+    const uint64_t n = blink::ticket_count(sc, group, shift, 0, &tiles_per_chunk);
     *n_tickets = n;
     if (!stage && !tile) return BLINK_OK;
     if (!stage || !tile) return BLINK_EINVAL;
-    const unsigned group = blink::ticket_group(sc);
     for (uint64_t t = 0; t < n; ++t) {
         unsigned ii, tt;
         blink::ticket_to_tile(t, group, tiles_per_chunk, static_cast<unsigned>(sc.inst.size()), &ii, &tt);
@@ -310,7 +310,7 @@ blink_status_t blink_schedule_test_skip_call(blink_schedule_t* s) {
 }
 
 blink_status_t blink_schedule_set_kernel(blink_schedule_t* s, int kernel) {
-    if (!s || kernel < 0 || kernel > 2) return BLINK_EINVAL;
+    if (!s || kernel < 0 || kernel > 3) return BLINK_EINVAL;
     s->kernel_choice = kernel;
     return BLINK_OK;
 }

@@ -150,7 +150,8 @@ blink_status_t claim_static_block(blink_schedule* h, const BlockLayout& l, hipSt
 // Tickets of a schedule whose tile grid is moved down by grid_shift elements.
 void count_tickets(blink_schedule* h, uint32_t grid_shift) {
     LaunchPlan& pl = h->plan;
-    pl.n_items = ticket_count(h->s, pl.tile_shift, grid_shift, &pl.tiles_per_chunk);
+    pl.n_items = ticket_count(h->s, ticket_group(h->s), pl.tile_shift, grid_shift, &pl.tiles_per_chunk);
+    pl.n_items_turns = ticket_count(h->s, 1, pl.tile_shift, grid_shift, &pl.tiles_per_chunk);
     pl.grid_shift = grid_shift;
 }
 
@@ -280,17 +281,23 @@ blink_status_t read_status(blink_schedule* h, blink_progress_t* out) {
     return BLINK_ESTUCK;
 }
 
-// Picking between the two kernels.  A schedule that both can run (no
-// dependencies, streaming size, sum) is served fastest by blink_consume on most
-// placements of the caller's buffers, but on some blink_consume loses a quarter
-// of its throughput and blink_stream, which is steadier, wins; which is which
-// depends on where the buffers lie in HBM, in ways addresses do not reveal.  So
-// the first kTrialCalls calls on such a schedule alternate between the two,
-// each timed with a pair of events on the caller's stream; the next call waits
-// for the last of them (the one time a call waits for the device, besides a
-// schedule's first) and the kernel with the smaller minimum serves the rest.
-// Both give the same bits.
-constexpr int kTrialCalls = 8;
+// Picking how a schedule is served.  A schedule without dependencies at
+// streaming size can run in up to three ways: on blink_consume (1), on
+// blink_stream where the operator is the sum and the stages fit it (2), and,
+// with several trees, on blink_consume with the trees taking turns chunk by
+// chunk instead of tile by tile (3).  Which is fastest depends on where the
+// buffers lie in HBM and how far apart the trees' shares are, in ways addresses
+// do not reveal: 1 wins on most placements and by far where the shares are a
+// power of two apart (8 x 256 MiB: 0.79 of the HBM peak against 0.73 for 3),
+// 2 is steadier where rank buffers are badly placed, 3 where the shares are
+// (8 x 117 MiB: 0.66 for 1, 0.73 for 3; sixteen gradient buckets of 64 KiB to
+// 400 MiB: 0.665 -> 0.69 overall).  So the first calls on such a schedule go
+// round the candidates, kTrialSamples times each, each call timed with a pair
+// of events on the caller's stream; the next call waits for the last of them
+// (the one time a call waits for the device, besides a schedule's first) and
+// the candidate with the smallest minimum serves the rest.  All give the same
+// bits.
+constexpr int kTrialSamples = 4;
 constexpr uint64_t kTrialMinBytes = 64ull << 20;  // smaller calls are too short to time against one another
 
 namespace {
@@ -302,15 +309,25 @@ void drop_trial_events(blink_schedule* h) {
     h->trial_events_made = false;
 }
 
-// 1 = blink_consume, 2 = blink_stream for this call; *timed: index of the event pair to put around it, or -1.
-int choose_kernel(blink_schedule* h, bool static_block, int* timed) {
+// How this call is served (1, 2 or 3, see above); *timed: index of the event
+// pair to put around it, or -1.  streams: the schedule can run on blink_stream;
+// can_stream: this call can (its operator is the sum); can_turns: way 3 exists.
+int choose_kernel(blink_schedule* h, bool static_block, bool streams, bool can_stream, bool can_turns, int* timed) {
     *timed = -1;
-    if (h->kernel_choice) return h->kernel_choice;
-    if (h->picked) return h->picked;
-    if (static_block || h->s.traffic_bytes < kTrialMinBytes) return 1;  // no trial: nothing may be created here / too short
-    if (h->trial_calls < kTrialCalls) {
+    auto allowed = [&](int way) { return way == 1 || (way == 2 && can_stream) || (way == 3 && can_turns); };
+    if (h->kernel_choice) return allowed(h->kernel_choice) ? h->kernel_choice : 1;
+    if (h->picked) return allowed(h->picked) ? h->picked : 1;
+    int ways[3], n_ways = 0;
+    ways[n_ways++] = 1;
+    if (streams) ways[n_ways++] = 2;
+    if (can_turns) ways[n_ways++] = 3;
+    // no trial: one way only / nothing may be created here / too short / a call
+    // with another operator than the schedule's trial is held with
+    if (n_ways == 1 || static_block || h->s.traffic_bytes < kTrialMinBytes || (streams && !can_stream)) return 1;
+    const int trial_calls = n_ways * kTrialSamples;
+    if (h->trial_calls < trial_calls) {
         if (!h->trial_events_made) {
-            for (void*& e : h->trial_event) {
+            for (int e = 0; e < 2 * trial_calls; ++e) {
                 hipEvent_t ev = nullptr;
                 if (hipEventCreate(&ev) != hipSuccess) {
                     (void)hipGetLastError();
@@ -318,29 +335,38 @@ int choose_kernel(blink_schedule* h, bool static_block, int* timed) {
                     h->picked = 1;
                     return 1;
                 }
-                e = ev;
+                h->trial_event[e] = ev;
             }
             h->trial_events_made = true;
         }
         *timed = h->trial_calls;
-        return 1 + (h->trial_calls & 1);
+        return ways[h->trial_calls % n_ways];
     }
     // All trial calls are launched: wait for the last of them (once per
-    // schedule, at its ninth call) and compare the fastest of each kernel's
-    // calls but its first (which carries what happens once: the code's first
-    // launch, tables not yet in any cache).  Kernels of a tenth of a millisecond
-    // differ by a few percent, which is also what the event pair around a single
-    // launch scatters by: hence three samples each, not one.
-    float best[2] = {1e30f, 1e30f};
-    bool ok = hipEventSynchronize(static_cast<hipEvent_t>(h->trial_event[2 * kTrialCalls - 1])) == hipSuccess;
-    for (int c = 0; ok && c < kTrialCalls; ++c) {
+    // schedule) and compare the fastest of each candidate's calls but its first
+    // (which carries what happens once: the code's first launch, tables not yet
+    // in any cache).  Kernels of a tenth of a millisecond differ by a few
+    // percent, which is also what the event pair around a single launch
+    // scatters by: hence three samples each, not one.
+    float best[3] = {1e30f, 1e30f, 1e30f};
+    bool ok = hipEventSynchronize(static_cast<hipEvent_t>(h->trial_event[2 * trial_calls - 1])) == hipSuccess;
+    for (int c = 0; ok && c < trial_calls; ++c) {
         float ms = 0.f;
         ok = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(h->trial_event[2 * c]),
                                  static_cast<hipEvent_t>(h->trial_event[2 * c + 1])) == hipSuccess;
-        if (c >= 2) best[c & 1] = std::min(best[c & 1], ms);
+        if (c >= n_ways) best[c % n_ways] = std::min(best[c % n_ways], ms);
     }
     if (!ok) (void)hipGetLastError();
-    h->picked = ok && best[1] < best[0] ? 2 : 1;
+    // The first way keeps the schedule unless another beats it by more than the
+    // 2 % by which such minima scatter from one trial to the next.
+    int fastest = 0;
+    float bar = best[0] * 0.98f;
+    for (int w = 1; ok && w < n_ways; ++w)
+        if (best[w] < bar) {
+            fastest = w;
+            bar = best[w];
+        }
+    h->picked = ways[fastest];
     drop_trial_events(h);
     return h->picked;
 }
@@ -410,7 +436,10 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     const LaunchPlan& pl = h->plan;
 
     int timed = -1;
-    const bool direct = pl.direct && redop == BLINK_SUM && choose_kernel(h, static_block, &timed) == 2;
+    const unsigned full_group = ticket_group(s);
+    const int way = choose_kernel(h, static_block, pl.direct, pl.direct && redop == BLINK_SUM,
+                                  !pl.wide && !s.has_deps && full_group > 1, &timed);
+    const bool direct = way == 2;
     KernelFn fn = pick_kernel(dtype, pl.flavour, pl.wide, direct);
     int& occ = h->occupancy[dtype == BLINK_FP32][direct];
     if (occ == 0) {
@@ -434,7 +463,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     if (h->wg_per_cu > 0) per_cu = std::min(occ, h->wg_per_cu);
     if (pl.wide && h->wg_per_cu == 0) per_cu = occ;
     unsigned long long max_grid = static_cast<unsigned long long>(per_cu) * h->n_cu;
-    const unsigned long long n_items = pl.n_items;
+    const unsigned long long n_items = way == 3 ? pl.n_items_turns : pl.n_items;
     // with dependencies no more waves than three time slots' worth of tickets can be busy
     if (s.has_deps) max_grid = std::min(max_grid, std::max<unsigned long long>(64, 3 * (n_items / s.n_slots + 1)));
     const unsigned long long grid = std::min<unsigned long long>(max_grid, n_items);
@@ -471,7 +500,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
     p.tiles_per_chunk = pl.tiles_per_chunk;
     p.tile_shift = pl.tile_shift;
     p.redop = static_cast<unsigned>(redop);
-    p.group = ticket_group(s);
+    p.group = way == 3 ? 1u : full_group;
     p.grid_shift = pl.grid_shift;
     p.n_inst = static_cast<unsigned>(s.inst.size());
     // Calls on a schedule without dependencies sweep the payload in alternating
@@ -525,7 +554,7 @@ blink_status_t execute(blink_schedule* h, void* const* bufs, int k, size_t n, bl
         }
     }
     h->last_grid = static_cast<unsigned>(grid);
-    h->last_kernel = direct ? 2 : 1;
+    h->last_kernel = way;
     if (static_block) return BLINK_OK;
     h->epoch += 1;
     if (static_items < n_items) {

@@ -123,7 +123,8 @@ inline unsigned ticket_group(const Schedule& s) {
 }
 
 // Number of tickets of a schedule for tiles of 2^tile_shift elements on a grid
-// moved down by grid_shift elements; *tiles_per_chunk receives the tile count
+// moved down by grid_shift elements, handed out in groups of `group` instances
+// (see ticket_to_tile); *tiles_per_chunk receives the tile count
 // of the instance that has most (every group of instances but the last gets
 // that many tickets per member).  The last group gets only as many per member
 // as its own largest instance has: with trees of equal weight every tree's
@@ -131,7 +132,8 @@ inline unsigned ticket_group(const Schedule& s) {
 // their holder a trip to the counter (25.6 MB shares in 4 MiB chunks: an
 // eighth of the tickets were such, and 8 % of the time).  Schedules with
 // dependencies keep the full count: their groups are single instances.
-inline uint64_t ticket_count(const Schedule& s, unsigned tile_shift, uint32_t grid_shift, uint32_t* tiles_per_chunk) {
+inline uint64_t ticket_count(const Schedule& s, unsigned group, unsigned tile_shift, uint32_t grid_shift,
+                             uint32_t* tiles_per_chunk) {
     const uint64_t tile = 1ull << tile_shift;
     auto tiles_of = [&](const StageInst& in) {
         return ((in.off + grid_shift + in.len + tile - 1) >> tile_shift) - ((in.off + grid_shift) >> tile_shift);
@@ -141,7 +143,6 @@ inline uint64_t ticket_count(const Schedule& s, unsigned tile_shift, uint32_t gr
     *tiles_per_chunk = static_cast<uint32_t>(most);
     const uint64_t n_inst = s.inst.size();
     if (s.has_deps || n_inst == 0) return n_inst * most;
-    const uint64_t group = ticket_group(s);
     const uint64_t first = (n_inst - 1) / group * group;  // the last group's first instance
     uint64_t last_most = 1;
     for (uint64_t i = first; i < n_inst; ++i) last_most = last_most > tiles_of(s.inst[i]) ? last_most : tiles_of(s.inst[i]);

@@ -21,6 +21,7 @@ struct LaunchPlan {
     uint32_t tiles_per_chunk = 1;  // most tiles any stage instance has
     uint32_t grid_shift = 0;       // elements the tile grid is moved down by (see execute)
     uint64_t n_items = 0;          // tickets per call
+    uint64_t n_items_turns = 0;    // the same when the trees take turns chunk by chunk (group 1)
     bool read_heavy = false;
     bool direct = false;           // the schedule CAN run on the streaming kernel (stream.hpp)
 };
@@ -50,14 +51,16 @@ struct blink_schedule {
     unsigned tile_override = 0;   // elements per tile requested by the caller (0 = automatic)
     int occupancy[2][2] = {};     // waves per CU of the kernel in use, per dtype and per (streaming kernel or not)
     unsigned last_grid = 0;
-    int last_kernel = 0;          // the kernel the latest call ran on: 1 = blink_consume, 2 = blink_stream
+    int last_kernel = 0;          // how the latest call ran: 1 = blink_consume, 2 = blink_stream, 3 = blink_consume, trees in turns
     int last_static_device = -1;  // device whose static block the latest call used; -1 = it used d_block
-    // Which of the two kernels serves a schedule that both can run (see execute):
-    int kernel_choice = 0;        // the caller's wish: 0 = pick the faster, 1 = blink_consume, 2 = blink_stream
+    // What serves a schedule that has the choice (see execute): blink_consume (1),
+    // blink_stream (2), or blink_consume with the trees taking turns chunk by
+    // chunk instead of tile by tile (3).
+    int kernel_choice = 0;        // the caller's wish: 0 = pick the fastest, else one of the three
     bool sweep_alternates = true; // calls on a schedule without dependencies walk the tiles in alternating directions
-    int picked = 0;               // the pick once made (1 or 2); 0 = not yet
-    int trial_calls = 0;          // timed calls launched so far (they alternate between the two kernels)
-    void* trial_event[16] = {};   // hipEvent_t pairs around the timed calls
+    int picked = 0;               // the pick once made (1, 2 or 3); 0 = not yet
+    int trial_calls = 0;          // timed calls launched so far (the candidates take turns)
+    void* trial_event[24] = {};   // hipEvent_t pairs around the timed calls
     bool trial_events_made = false;
 };
 

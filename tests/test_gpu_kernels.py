@@ -54,7 +54,7 @@ def _trees(name, root):
     return top.k, bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, root)
 
 
-@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("kernel", [1, 2, 3])
 @pytest.mark.parametrize("name,root,n,chunk", CASES)
 def test_each_kernel_against_the_oracle(name, root, n, chunk, kernel):
     dev, stream = _dev()
@@ -70,7 +70,8 @@ def test_each_kernel_against_the_oracle(name, root, n, chunk, kernel):
         bufs = [torch.from_numpy(a).to(dev) for a in x]
         bl.blink_allreduce(bufs, n, code, sched, stream)
         torch.cuda.synchronize()
-        expected_kernel = 1 if name == "deep12" else kernel
+        one_tree = name.startswith("deep") or name in ("k2", "chain5")
+        expected_kernel = 1 if (name == "deep12" or (kernel == 3 and (one_tree or name == "k16"))) else kernel
         assert sched.last_kernel == expected_kernel
         for r, b in enumerate(bufs):
             got = b.cpu().numpy()
@@ -112,7 +113,7 @@ def test_streaming_kernel_on_reduce_and_broadcast(coll):
             assert np.array_equal(b.cpu().numpy(), x[0])
 
 
-def test_automatic_choice_times_both_and_settles():
+def test_automatic_choice_times_every_way_and_settles():
     dev, stream = _dev()
     top = si.hybrid_cube_mesh()
     n, chunk, k = 1 << 24, 1 << 18, 8
@@ -122,15 +123,28 @@ def test_automatic_choice_times_both_and_settles():
     x = [si.hash_payload(23, r, 0, n, "int32") for r in range(k)]
     want = ox.allreduce_int32_definition(x)
     seen = []
-    for call in range(12):
+    for call in range(16):
         bufs = [torch.from_numpy(a).to(dev) for a in x]
         bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream)
         seen.append(sched.last_kernel)
         torch.cuda.synchronize()
         for b in bufs:
             assert np.array_equal(b.cpu().numpy(), want), call
-    assert seen[:8] == [1, 2] * 4                    # the timed calls alternate
-    assert len(set(seen[8:])) == 1 and seen[8] in (1, 2)   # then one kernel serves
+    # the timed calls go round the three ways (either kernel, and the first with
+    # the trees taking turns chunk by chunk), then one of them serves
+    assert seen[:12] == [1, 2, 3] * 4
+    assert len(set(seen[12:])) == 1 and seen[12] in (1, 2, 3)
+    # one tree: nothing to take turns, two ways
+    one = bl.blink_trees_from_arrays(k, [0], [_deep_tree(k)], [1.0])
+    sched = bl.blink_make_schedule(one, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+    seen = []
+    for call in range(10):
+        bufs = [torch.from_numpy(a).to(dev) for a in x]
+        bl.blink_allreduce(bufs, n, bl.BLINK_INT32, sched, stream)
+        seen.append(sched.last_kernel)
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs[k - 1].cpu().numpy(), want), call
+    assert seen[:8] == [1, 2] * 4 and len(set(seen[8:])) == 1 and seen[8] in (1, 2)
     # a small payload is not worth a trial
     m = 1 << 12
     small = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, m, 1 << 10, bl.BLINK_FUSE_TREE)
@@ -141,7 +155,7 @@ def test_automatic_choice_times_both_and_settles():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("kernel", [1, 2, 3])
 def test_alternating_sweep_gives_the_same_bits_as_forward_calls(kernel):
     """Every other call on a dependency-free schedule goes through the tiles
     backwards (the default); with that switched off all go forwards.  Four calls
@@ -174,7 +188,7 @@ def test_alternating_sweep_gives_the_same_bits_as_forward_calls(kernel):
             assert np.array_equal(results[True][call][r], summed.view(np.uint32)), (call, r)
 
 
-@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("kernel", [1, 2, 3])
 @pytest.mark.parametrize("past", [(16,) * 8, (512,) * 8, (1008,) * 8, (0, 16, 32, 48, 512, 528, 1008, 64)])
 def test_rank_buffers_that_do_not_start_on_1k_boundaries(kernel, past):
     """Rank buffers that are views into larger ones.  Where all of them start

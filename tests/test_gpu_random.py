@@ -89,11 +89,11 @@ def streaming_case(seed):
 
 @pytest.mark.parametrize("seed", range(8))
 def test_random_trees_at_streaming_size_over_three_calls(dev, seed):
-    """Either kernel, three calls in place (the second goes through the tiles
+    """Any of the three ways, three calls in place (the second goes through the tiles
     backwards): after call c every rank holds the oracle's sum times k^(c-1),
     modulo 2^32, and no byte outside the views has changed."""
     k, roots, parents, w, n, chunk, past = streaming_case(seed)
-    kernel = 1 + seed % 2
+    kernel = 1 + seed % 3      # a way the schedule does not have falls back to the first
     trees = bl.blink_trees_from_arrays(k, roots, parents, w)
     sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
     sched.set_kernel(kernel)

@@ -365,3 +365,19 @@ def test_sweep_switch_takes_zero_or_one():
     assert lib.blink_schedule_set_sweep(sched._h, 2) == bl.BLINK_EINVAL
     assert lib.blink_schedule_set_sweep(sched._h, -1) == bl.BLINK_EINVAL
     assert lib.blink_schedule_set_sweep(None, 1) == bl.BLINK_EINVAL
+
+
+def test_kernel_switch_takes_zero_to_three():
+    """blink_schedule_set_kernel: automatic, or one of the three ways a schedule
+    can be served; host-side state only."""
+    from paper_1910_04940_amd import binding
+    top = si.hybrid_cube_mesh()
+    trees = bl.blink_pack_trees(top.k, top.src, top.dst, top.cap, 0)
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, 1 << 16, 1 << 12, bl.BLINK_FUSE_TREE)
+    for way in (0, 1, 2, 3, 0):
+        sched.set_kernel(way)
+    assert sched.last_kernel == 0                        # nothing has run yet
+    lib = binding.lib()
+    assert lib.blink_schedule_set_kernel(sched._h, 4) == bl.BLINK_EINVAL
+    assert lib.blink_schedule_set_kernel(sched._h, -1) == bl.BLINK_EINVAL
+    assert lib.blink_schedule_set_kernel(None, 1) == bl.BLINK_EINVAL
