@@ -160,7 +160,7 @@ void count_tickets(blink_schedule* h, uint32_t grid_shift) {
 // The tile is large enough that a ticket moves about kTicketBytes.  A payload
 // too small to give a streaming grid 16 such tickets per CU is latency-bound
 // instead ("wide"): then all the waves that fit are used and the tile shrinks
-// until about every other wave has one.  (Measured on 8 ranks, 4 trees: at 11
+// (see below).  (Measured on 8 ranks, 4 trees: at 11
 // tickets per CU the wide launch takes 52 us and the streaming one 72, at 16
 // they tie at 79, at 18 it is 157 against 130, at 23 161 against 143.)
 blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
@@ -216,8 +216,35 @@ blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
         // 42 -> see the measurements).
         if (s.has_deps)
             while (tile > kMinTile && work / s.n_slots / tile < 64) tile /= 2;
-        else
-            while (tile > kMinTile && work / tile < static_cast<uint64_t>(occ) * h->n_cu / 2) tile /= 2;
+        else {
+            // Without dependencies the tickets of such a payload are dealt out in
+            // rounds over the waves that fit (drawn, so many small ones would queue
+            // at the counter; see execute), and the call lasts as long as the wave
+            // with most of them: a tile size costs its rounds times the tile plus
+            // what a ticket costs besides its elements (about 2.5 us of latencies,
+            // the time in which a wave among a thousand moves 15 KB).
+            // Measured, 8 ranks x 4 trees on 1,024 waves, 2,048 -> 1,024-element
+            // tiles: 2.7 M elements per rank (1.3 -> 2.6 tickets per wave) 43.8 ->
+            // 38.4 us, 4.2 M (2.0 -> 4.0) 59.7 -> 52.7 us, but 3.2 M (1.5 -> 3.05)
+            // 42.9 -> 43.3 us: the last round counts whole.
+            const uint64_t waves = static_cast<uint64_t>(occ) * h->n_cu;
+            unsigned best = tile;
+            uint64_t best_cost = ~0ull;
+            for (unsigned cand = tile; cand >= kMinTile; cand /= 2) {
+                unsigned shift = 0;
+                while ((1u << shift) < cand) ++shift;
+                uint32_t most = 0;
+                const uint64_t tickets = ticket_count(s, ticket_group(s), shift, 0, &most);
+                if (tickets / std::min(waves, tickets) > 4) break;  // these would be drawn
+                const uint64_t rounds = (tickets + waves - 1) / waves;
+                const uint64_t cost = rounds * (cand + 15360 / bytes_per_elem);
+                if (cost < best_cost) {
+                    best = cand;
+                    best_cost = cost;
+                }
+            }
+            tile = best;
+        }
     }
     // The streaming kernel (stream.hpp) takes schedules without dependencies all
     // of whose stages have a stack program within its limits.
