@@ -412,10 +412,19 @@ __device__ __forceinline__ void run_scalar(unsigned* __restrict__ slots, ConstPa
 //          so the hand-over needs no L2 write-back or invalidate, only "my
 //          stores have completed" before the counter is bumped.
 // COLS: the column budget (LDS slots per lane).
+// The kernel takes all 256 vector registers and 96 accumulation registers, so
+// one wave per SIMD fits (4 per CU).  The 16-column variant, for payloads too
+// small to keep the memory system busy with that, is held to half the register
+// file (the second launch bound: two waves per SIMD; about 160 registers then
+// live in per-lane scratch memory): twice the waves hide more latency than the
+// spills cost (8 ranks x 4 trees, 1 M elements per rank 17.9 -> 15.4 us, 4.2 M
+// 52.0 -> 45.7 us); three per SIMD lose again (4.2 M: 52.1 us), and where
+// stages wait for one another the spills cost more than the waves bring.
 // The by-value argument is only there to size the kernel-argument segment; it is
 // read through the constant address space (see ConstParams).
 template <typename T, int FLAVOUR, int COLS>
-__global__ __launch_bounds__(kLanes) void blink_consume(const KParams) {
+__global__ __launch_bounds__(kLanes, COLS == kColumnsMany && FLAVOUR != kHandOver ? 2 : 1) void blink_consume(
+    const KParams) {
     __shared__ U4 slots[COLS * kLanes];  // 16 or 32 KiB: COLS columns per lane
     constexpr int LD = Policy<FLAVOUR>::kLoad;
     constexpr int ST = Policy<FLAVOUR>::kStore;
