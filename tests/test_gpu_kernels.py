@@ -224,3 +224,30 @@ def test_rank_buffers_that_do_not_start_on_1k_boundaries(kernel, past):
     for b in bufs:
         b.zero_()
     assert int(torch.count_nonzero(slab)) == 0, "bytes outside the rank buffers were written"
+
+
+@pytest.mark.parametrize("n", [1_500_003, 2_713_001, 4_200_005, 6_000_002])
+def test_payloads_whose_tickets_are_dealt_out_in_several_rounds(n):
+    """Between the smallest payloads (one ticket per wave) and the streaming
+    sizes the tickets are dealt out over every wave that fits, two to five each,
+    on the 16-column kernel with two waves per SIMD.  Two calls in place, both
+    element types, against the oracle."""
+    dev, stream = _dev()
+    top = si.hybrid_cube_mesh()
+    k, chunk = 8, 1 << 18
+    trees = bl.blink_pack_trees(k, top.src, top.dst, top.cap, 0)
+    roots, parents, w = trees.as_lists()
+    sched = bl.blink_make_schedule(trees, bl.BLINK_OP_ALLREDUCE, n, chunk, bl.BLINK_FUSE_TREE)
+    for dtype, code in (("int32", bl.BLINK_INT32), ("fp32", bl.BLINK_FP32)):
+        x = [si.hash_payload(41, r, 0, n, dtype) for r in range(k)]
+        bufs = [torch.from_numpy(a).to(dev) for a in x]
+        want = x
+        for call in range(2):
+            bl.blink_allreduce(bufs, n, code, sched, stream)
+            torch.cuda.synchronize()
+            summed = ox.tree_order_allreduce(want, roots, parents, w)
+            want = [summed.copy() for _ in range(k)]
+            for r, b in enumerate(bufs):
+                assert np.array_equal(b.cpu().numpy().view(np.uint32), summed.view(np.uint32)), (dtype, call, r)
+    assert sched.last_kernel == 1
+    assert sched.status()[0] == bl.BLINK_OK
