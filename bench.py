@@ -324,8 +324,14 @@ def main():
     SETUP_CALLS = 13
     say("inputs are on the device")
     restore()
-    for _ in range(SETUP_CALLS):
+    if args.progress:
+        torch.cuda.synchronize()
+        say("inputs restored")
+    for i in range(SETUP_CALLS):
         step()
+        if args.progress:           # slow, profiled runs: say where they are, call by call
+            torch.cuda.synchronize()
+            say(f"set-up call {i + 1} of {SETUP_CALLS} done")
     torch.cuda.synchronize()
     say("set-up calls done")
     since_restore = 0
