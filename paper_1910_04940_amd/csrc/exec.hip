@@ -43,7 +43,7 @@ uint64_t next_schedule_id() { return g_next_id.fetch_add(1); }
 // ---- host side ------------------------------------------------------------------------
 namespace {
 
-void drop_trial_events(blink_schedule* h);  // below, with the choice between the two kernels
+void drop_trial_events(blink_schedule* h);  // below, with the choice among the ways to serve a schedule
 
 #define BLINK_HIP(call)                                                                   \
     do {                                                                                  \
@@ -160,9 +160,11 @@ void count_tickets(blink_schedule* h, uint32_t grid_shift) {
 // The tile is large enough that a ticket moves about kTicketBytes.  A payload
 // too small to give a streaming grid 16 such tickets per CU is latency-bound
 // instead ("wide"): then all the waves that fit are used and the tile shrinks
-// (see below).  (Measured on 8 ranks, 4 trees: at 11
-// tickets per CU the wide launch takes 52 us and the streaming one 72, at 16
-// they tie at 79, at 18 it is 157 against 130, at 23 161 against 143.)
+// (see below).  (Measured on 8 ranks, 4 trees, when the threshold was set, with
+// one wave per SIMD: at 11 tickets per CU the wide launch took 52 us and the
+// streaming one 72, at 16 they tied at 79, at 18 it was 157 against 130.  With
+// two waves per SIMD the wide launch wins by more below the threshold and still
+// loses above it: 10 M elements per rank 132 us against 121.)
 blink_status_t make_plan(blink_schedule* h, blink_dtype_t dtype) {
     LaunchPlan& pl = h->plan;
     if (pl.made) return BLINK_OK;
