@@ -299,6 +299,9 @@ class Schedule:
         return stage, tile
 
     def set_kernel(self, kernel: int) -> None:
+        """0 = the library times the ways it can serve this schedule and keeps the
+        fastest; 1 = ticket-drawing kernel, 2 = streaming kernel, 3 = ticket-drawing
+        kernel with the trees taking turns chunk by chunk (see blink.h)."""
         _check(lib().blink_schedule_set_kernel(self._h, kernel), "blink_schedule_set_kernel")
 
     def set_sweep(self, alternate: bool) -> None:
@@ -306,6 +309,7 @@ class Schedule:
 
     @property
     def last_kernel(self) -> int:
+        """The way the latest call on this schedule ran (1, 2 or 3; 0 before the first)."""
         return lib().blink_schedule_last_kernel(self._h)
 
     def status(self) -> Tuple[int, dict]:
